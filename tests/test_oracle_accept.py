@@ -1,0 +1,246 @@
+"""Pins for oracle/accept.py (CPU only).
+
+Each test checks the oracle against something fixed outside it: the exactness
+claim of Sec. 2.2 / 3.2 (output distribution == target distribution), closed
+forms that follow from Eq. 2-3, and the special cases of Alg. 1."""
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import accept as A
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_logits(rng, *shape, scale=1.5):
+    return rng.normal(0.0, scale, size=shape)
+
+
+def _softmax(z):
+    # scipy's routine, not the oracle's
+    from scipy.special import softmax
+    return softmax(np.asarray(z, dtype=np.float64), axis=-1)
+
+
+def _chi2_ok(counts, probs, alpha=1e-4):
+    n = counts.sum()
+    chi2 = ((counts - n * probs) ** 2 / (n * probs)).sum()
+    return stats.chi2.sf(chi2, df=len(probs) - 1) > alpha, chi2
+
+
+@pytest.mark.parametrize("mode", ["dense_q", "one_hot"])
+def test_first_token_distribution_is_target(mode):
+    """Sec. 3.2: the emitted token is distributed exactly as p, whatever q is."""
+    rng = np.random.default_rng(11)
+    V, N = 16, 100_000
+    z = _rand_logits(rng, 2, V)
+    ql = _rand_logits(rng, 1, V)
+    p = _softmax(z[0])
+    q = _softmax(ql[0])
+    drafts = rng.choice(V, size=N, p=q)
+    ua, us = rng.random(N), rng.random(N)
+    counts = np.zeros(V)
+    for n in range(N):
+        if mode == "dense_q":
+            r = A.verify_sequence(z, [drafts[n]], [ua[n]], us[n], q_logits=ql)
+        else:   # deterministic draft (the paper's case): fixed token, q one-hot
+            r = A.verify_sequence(z, [3], [ua[n]], us[n], q_logits=None)
+        counts[r.tokens[0]] += 1
+    ok, chi2 = _chi2_ok(counts, p)
+    assert ok, chi2
+
+
+def test_wrong_rule_fails_chi_square():
+    """The chi-square pin has power: dropping the residual's 'minus q' is caught."""
+    rng = np.random.default_rng(11)
+    V, N = 16, 100_000
+    z = _rand_logits(rng, 2, V)
+    ql = _rand_logits(rng, 1, V)
+    p, q = _softmax(z[0]), _softmax(ql[0])
+    drafts = rng.choice(V, size=N, p=q)
+    ua, us = rng.random(N), rng.random(N)
+    counts = np.zeros(V)
+    for n in range(N):
+        a = drafts[n]
+        if ua[n] < min(1.0, p[a] / q[a]):
+            counts[a] += 1
+        else:                                   # planted mistake: resample from p, not max(0,p-q)
+            counts[A.inverse_cdf(p, us[n])[0]] += 1
+    ok, _ = _chi2_ok(counts, p)
+    assert not ok
+
+
+def test_two_token_joint_matches_ancestral_sampling():
+    """Alg. 1 on a toy Markov 'policy': the joint law of the first two generated
+    tokens equals p(a|start) p(b|a)."""
+    rng = np.random.default_rng(5)
+    V, N = 6, 60_000
+    Z = _rand_logits(rng, V, V)                       # Z[prev] = logits of next
+    P = _softmax(Z)
+    start = 2
+    joint = np.zeros((V, V))
+    table = rng.integers(0, V, size=(V, 3))           # deterministic 'pool': draft block per last token
+
+    def next_logits(y, d):
+        toks = [y[-1]] + list(d)
+        return Z[toks]
+
+    u = rng.random(8 * N)
+    it = iter(u)
+    for _ in range(N):
+        y, _steps = A.rollout(next_logits, lambda y: table[y[-1]], [start], 3, lambda: next(it))
+        joint[y[1], y[2]] += 1
+    expect = (P[start][:, None] * P).ravel()
+    ok, chi2 = _chi2_ok(joint.ravel(), expect)
+    assert ok, chi2
+
+
+def test_acceptance_probability_closed_form():
+    """P(accept) = sum_x min(p,q) for x~q; = p(x~) for a deterministic draft;
+    the rejected mass is 1 - sum min(p,q)."""
+    rng = np.random.default_rng(3)
+    V, N = 12, 80_000
+    z, ql = _rand_logits(rng, 2, V), _rand_logits(rng, 1, V)
+    p, q = _softmax(z[0]), _softmax(ql[0])
+    drafts = rng.choice(V, size=N, p=q)
+    ua, us = rng.random(N), rng.random(N)
+    acc = sum(A.verify_sequence(z, [drafts[n]], [ua[n]], us[n], q_logits=ql).n_accepted
+              for n in range(N))
+    expect = np.minimum(p, q).sum()
+    assert abs(acc / N - expect) < 4 * np.sqrt(expect * (1 - expect) / N)
+    acc1 = sum(A.verify_sequence(z, [7], [ua[n]], us[n]).n_accepted for n in range(N))
+    assert abs(acc1 / N - p[7]) < 4 * np.sqrt(p[7] * (1 - p[7]) / N)
+
+
+def test_residual_of_deterministic_draft_is_eq3():
+    """Rejected deterministic draft: recovered token follows Eq. 3 exactly:
+    never the draft itself, and inverse-CDF over p with x~ removed."""
+    rng = np.random.default_rng(9)
+    V = 10
+    z = _rand_logits(rng, 2, V)
+    p = _softmax(z[0])
+    a = int(np.argmax(p))
+    r_eq3 = p.copy()
+    r_eq3[a] = 0.0
+    r_eq3 /= 1.0 - p[a]
+    edges = np.concatenate([[0.0], np.cumsum(r_eq3)])
+    for us in np.linspace(0.001, 0.999, 97):
+        r = A.verify_sequence(z, [a], [0.999999], us)       # u >= p(a): rejected
+        assert r.n_accepted == 0 and len(r.tokens) == 1 and r.tokens[0] != a
+        x = r.tokens[0]
+        assert edges[x] <= us * edges[-1] < edges[x + 1] + 1e-15
+
+
+def test_q_equal_p_always_accepts():
+    rng = np.random.default_rng(4)
+    V, k = 9, 5
+    z = _rand_logits(rng, k + 1, V)
+    for _ in range(200):
+        d = rng.integers(0, V, size=k)
+        r = A.verify_sequence(z, d, rng.random(k), rng.random(), q_logits=z[:k].copy())
+        assert r.n_accepted == k and r.tokens[:k] == list(d) and len(r.tokens) == k + 1
+
+
+def test_one_hot_q_equals_none_q_bit_for_bit():
+    rng = np.random.default_rng(6)
+    V, k = 33, 4
+    for _ in range(300):
+        z = _rand_logits(rng, k + 1, V)
+        d = rng.integers(0, V, size=k)
+        ua, us = rng.random(k), rng.random()
+        ql = np.full((k, V), -np.inf)
+        ql[np.arange(k), d] = 0.0
+        with np.errstate(invalid="ignore"):
+            r1 = A.verify_sequence(z, d, ua, us, q_logits=ql)
+        r0 = A.verify_sequence(z, d, ua, us, q_logits=None)
+        assert (r0.n_accepted, r0.tokens) == (r1.n_accepted, r1.tokens)
+
+
+def test_greedy_drafts_fully_accepted_at_temperature_zero():
+    """Eq. 2 with a one-hot p: drafts on the arg-max path are accepted with
+    probability 1 and the bonus is the next arg-max."""
+    rng = np.random.default_rng(8)
+    V, k = 50, 6
+    z = _rand_logits(rng, k + 1, V)
+    d = np.argmax(z[:k], axis=1)
+    r = A.verify_sequence(z, d, rng.random(k), rng.random(), temperature=0.0)
+    assert r.n_accepted == k and r.tokens == list(d) + [int(np.argmax(z[k]))]
+    d2 = d.copy()
+    d2[2] = (d2[2] + 1) % V                       # off the greedy path at position 3
+    r = A.verify_sequence(z, d2, rng.random(k), rng.random(), temperature=0.0)
+    assert r.n_accepted == 2 and r.tokens == list(d[:2]) + [int(d[2])]
+
+
+def test_empty_draft_is_plain_sampling():
+    """Alg. 1's first branch: k = 0 samples x ~ pi(.|y); compared with an
+    independently written inverse-CDF draw (numpy searchsorted on scipy softmax)."""
+    rng = np.random.default_rng(10)
+    V = 40
+    for emit_bonus in (True, False):
+        for _ in range(200):
+            z = _rand_logits(rng, 1, V)
+            us = rng.random()
+            r = A.verify_sequence(z, [], [], us, emit_bonus=emit_bonus)
+            C = np.cumsum(_softmax(z[0]))
+            assert r.n_accepted == 0 and r.tokens == [int(np.searchsorted(C, us * C[-1], side="right"))]
+            assert A.plain_sample(z[0], us) == r.tokens[0]
+
+
+def test_eos_and_bonus_conventions():
+    V = 5
+    z = np.zeros((3, V))
+    z[:, 1] = 50.0                                # p ~ one-hot at token 1
+    r = A.verify_sequence(z, [1, 1], [0.5, 0.5], 0.3, eos_id=1)
+    assert r.tokens == [1] and r.n_accepted == 1          # accepted EOS ends the block
+    r = A.verify_sequence(z, [1, 1], [0.5, 0.5], 0.3, emit_bonus=False)
+    assert r.tokens == [1, 1] and r.n_accepted == 2
+    r = A.verify_sequence(z, [1, 1], [0.5, 0.5], 0.3, emit_bonus=True)
+    assert r.tokens == [1, 1, 1]
+
+
+def test_temperature_scaling():
+    """p_t is the distribution after temperature scaling (Sec. 3.2)."""
+    rng = np.random.default_rng(12)
+    z = _rand_logits(rng, 30)
+    for T in (0.5, 1.0, 2.0):
+        np.testing.assert_allclose(A.target_probs(z, T), _softmax(z / T), rtol=1e-13)
+    assert A.target_probs(np.array([1.0, 3.0, 3.0]), 0.0).tolist() == [0.0, 1.0, 0.0]
+
+
+def test_expected_emitted_geometric():
+    """With i.i.d. per-position acceptance a, E[emitted] = (1 - a^(k+1)) / (1 - a)."""
+    rng = np.random.default_rng(13)
+    V, k, N = 4, 8, 20_000
+    a = 0.7
+    z = np.log(np.array([a, (1 - a) / 3, (1 - a) / 3, (1 - a) / 3]))[None].repeat(k + 1, 0)
+    tot = sum(len(A.verify_sequence(z, [0] * k, rng.random(k), rng.random()).tokens) for _ in range(N))
+    expect = (1 - a ** (k + 1)) / (1 - a)
+    assert abs(tot / N - expect) < 0.05
+
+
+def test_paper_metric_identities():
+    """The paper's own numbers fix what 'acceptance length' counts: tokens emitted per
+    verify step including the recovered/bonus token (Sec. 4.2), so that
+    acceptance_rate = (acceptance_length - 1) / draft_length (Tab. 2), and Eq. 1
+    reproduces the reported time reduction."""
+    rows, hist, eq1 = [], [], None
+    for line in open(os.path.join(GOLD, "paper_table2_spec_metrics.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "hist":
+            hist.append((int(f[1]), float(f[2]) / 100))
+        elif f[0] == "eq1":
+            eq1 = [float(x) for x in f[1:]]
+        else:
+            rows.append([float(x) for x in f[1:]])
+    for acc_len, draft_len, rate in rows:
+        assert abs((acc_len - 1) / draft_len * 100 - rate) < 0.15
+    mean = sum(n * w for n, w in hist)
+    assert abs(mean - rows[0][0]) < 0.01
+    s0, s1, t0, t1, reported = eq1
+    alpha = 1 - s1 / s0
+    mu = (t1 / s1) / (t0 / s0) - 1
+    assert abs((1 - (1 - alpha) * (1 + mu)) * 100 - reported) < 0.15
