@@ -1,0 +1,381 @@
+// C ABI of libbubblespec: argument validation, workspace carving and kernel sequencing of one
+// speculative-verification step (Alg. 1 of the paper; see include/bubblespec.h for the contract).
+#include "common.h"
+#include <new>
+#include <string>
+#include <vector>
+
+struct bs_ctx {
+  Shape s;
+  KvView kv;
+  int B_max, k_max, M_max;
+  std::vector<const float*> attn_norm, mlp_norm;
+  std::vector<const void*> wqkv, wo, w_gate_up, w_down;
+  std::vector<void*> k_pages, v_pages;
+  const void *embed, *lm_head;
+  const float* final_norm;
+  // workspace
+  Plan plan;
+  float* h;            // residual stream  [M_max, d] float32
+  void* a;             // normed rows      [M_max, d]
+  void* qkv;           // [M_max, (Hq+2Hkv) D]
+  void* attn_out;      // [M_max, Hq D]
+  void* act;           // [M_max, F]
+  void* hf;            // final-norm rows  [M_max, d]
+  void* attn_scratch;
+  float* full_logits;  // float32 models only: [M_max, V]
+  SamplerBufs sb;
+  int n_vtiles;
+  // pool
+  int n_prompts = 0, n_rollouts = 0;
+  const int32_t* pool_tokens = nullptr;
+  const int64_t* rollout_offsets = nullptr;
+  const int32_t* prompt_rollout_begin = nullptr;
+  // state
+  bool verify_pending = false;
+  int last_B = 0, last_k_max = 0;
+  std::string err;
+};
+
+namespace {
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T> T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+size_t elt(int dtype) { return dtype == BS_F32 ? 4 : 2; }
+
+bs_status check_desc(const bs_model_desc* d, int B_max, int k_max) {
+  if (!d) return BS_EINVAL;
+  if (d->dtype != BS_F32 && d->dtype != BS_BF16) return BS_EINVAL;
+  if (d->n_layers < 1 || d->d_model < 64 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 64 || d->vocab < 2)
+    return BS_ESHAPE;
+  if (d->head_dim != 64 && d->head_dim != 128) return BS_ESHAPE;
+  if (d->d_model % 64 || d->d_ffn % 64 || d->n_q_heads % d->n_kv_heads) return BS_ESHAPE;
+  if (B_max < 1 || B_max > 4096 || k_max < 0 || k_max > BS_MAX_K) return BS_ESHAPE;
+  if (!(d->rms_eps >= 0.f) || !(d->rope_theta > 0.f)) return BS_EINVAL;
+  // bf16 attention packs the (k_max+1)*G query rows of one KV head into at most four 32-row MFMA tiles
+  if (d->dtype == BS_BF16 && (k_max + 1) * (d->n_q_heads / d->n_kv_heads) > 128) return BS_ESHAPE;
+  return BS_OK;
+}
+
+// Lays the workspace out; with base == nullptr only measures it.
+size_t carve(bs_ctx* c, char* base) {
+  Carver w{base};
+  const Shape& s = c->s;
+  const int B = c->B_max, M = c->M_max;
+  Plan& p = c->plan;
+  p.status = w.take<int32_t>(64);
+  p.n_rows = w.take<int32_t>(64);
+  p.row_start = w.take<int32_t>(B + 1);
+  p.draft_start = w.take<int32_t>(B + 1);
+  p.seq_k = w.take<int32_t>(B);
+  p.seq_c = w.take<int32_t>(B);
+  p.seq_slot = w.take<int32_t>(B);
+  p.row_seq = w.take<int32_t>(M);
+  p.row_pos = w.take<int32_t>(M);
+  p.row_tok = w.take<int32_t>(M);
+  p.row_target = w.take<int32_t>(M);
+  c->h = w.take<float>((size_t)M * s.d);
+  c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));
+  c->qkv = w.take<char>((size_t)M * s.Nqkv() * elt(s.dtype));
+  c->attn_out = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
+  c->act = w.take<char>((size_t)M * s.F * elt(s.dtype));
+  c->hf = w.take<char>((size_t)M * s.d * elt(s.dtype));
+  c->attn_scratch = w.take<char>(attention_scratch_bytes(s, B, c->k_max));
+  c->n_vtiles = lmhead_vtiles(s.V);
+  SamplerBufs& sb = c->sb;
+  sb.part_max = w.take<float>((size_t)c->n_vtiles * M);
+  sb.part_sum = w.take<float>((size_t)c->n_vtiles * M);
+  sb.part_arg = w.take<int32_t>((size_t)c->n_vtiles * M);
+  sb.z_target = w.take<float>(M);
+  sb.q_lse = w.take<float>(M);
+  sb.q_target = w.take<float>(M);
+  sb.sel_row = w.take<int32_t>(B);
+  sb.sel_mode = w.take<int32_t>(B);
+  sb.sel_qrow = w.take<int32_t>(B);
+  sb.sel_tok = w.take<int32_t>(B);
+  if (s.dtype == BS_F32) {
+    c->full_logits = w.take<float>((size_t)M * s.V);
+    sb.sel_logits = nullptr;
+  } else {
+    c->full_logits = nullptr;
+    sb.sel_logits = w.take<float>((size_t)B * s.V);
+  }
+  return (w.off + 255) & ~(size_t)255;
+}
+
+void fill_shape(bs_ctx* c, const bs_model_desc* d, int B_max, int k_max) {
+  c->s = Shape{d->n_layers, d->d_model, d->n_q_heads, d->n_kv_heads, d->head_dim, d->d_ffn, d->vocab, d->dtype,
+               d->rms_eps, d->rope_theta};
+  c->B_max = B_max;
+  c->k_max = k_max;
+  c->M_max = B_max * (k_max + 1);
+}
+
+bs_status fail(bs_ctx* c, bs_status st, const char* msg) {
+  if (c) c->err = msg;
+  return st;
+}
+
+bs_status check_hip(bs_ctx* c) {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return BS_OK;
+  c->err = std::string("HIP: ") + hipGetErrorString(e);
+  return BS_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bs_workspace_bytes(const bs_model_desc* desc, int B_max, int k_max) {
+  if (check_desc(desc, B_max, k_max) != BS_OK) return 0;
+  bs_ctx tmp;
+  fill_shape(&tmp, desc, B_max, k_max);
+  return carve(&tmp, nullptr);
+}
+
+bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_desc* kv, void* workspace,
+                    size_t workspace_bytes, int B_max, int k_max, void* stream, bs_ctx** out) {
+  if (!out) return BS_EINVAL;
+  *out = nullptr;
+  if (!desc || !w || !kv || !workspace) return BS_EINVAL;
+  bs_status st = check_desc(desc, B_max, k_max);
+  if (st != BS_OK) return st;
+  if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->mlp_norm ||
+      !w->w_gate_up || !w->w_down)
+    return BS_EINVAL;
+  if (!kv->k_pages || !kv->v_pages || !kv->block_table || !kv->ctx_len) return BS_EINVAL;
+  if (kv->n_pages < 1 || kv->n_slots < 1 || kv->max_pages_per_seq < 1) return BS_ESHAPE;
+  if (((uintptr_t)workspace & 255) != 0) return BS_EINVAL;
+  bs_ctx* c = new (std::nothrow) bs_ctx();
+  if (!c) return BS_EINVAL;
+  fill_shape(c, desc, B_max, k_max);
+  if (carve(c, nullptr) > workspace_bytes) { delete c; return BS_ECAPACITY; }
+  carve(c, (char*)workspace);
+  const int L = desc->n_layers;
+  for (int l = 0; l < L; ++l) {
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->mlp_norm[l] || !w->w_gate_up[l] || !w->w_down[l] ||
+        !kv->k_pages[l] || !kv->v_pages[l]) { delete c; return BS_EINVAL; }
+    c->attn_norm.push_back(w->attn_norm[l]);
+    c->mlp_norm.push_back(w->mlp_norm[l]);
+    c->wqkv.push_back(w->wqkv[l]);
+    c->wo.push_back(w->wo[l]);
+    c->w_gate_up.push_back(w->w_gate_up[l]);
+    c->w_down.push_back(w->w_down[l]);
+    c->k_pages.push_back(kv->k_pages[l]);
+    c->v_pages.push_back(kv->v_pages[l]);
+  }
+  c->embed = w->embed;
+  c->lm_head = w->lm_head;
+  c->final_norm = w->final_norm;
+  c->kv = KvView{kv->n_pages, kv->n_slots, kv->max_pages_per_seq, kv->block_table, kv->ctx_len};
+  launch_clear_status(c->plan.status, (hipStream_t)stream);
+  st = check_hip(c);
+  if (st != BS_OK) { delete c; return st; }
+  *out = c;
+  return BS_OK;
+}
+
+void bs_destroy(bs_ctx* ctx) { delete ctx; }
+
+const char* bs_last_error(const bs_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+bs_status bs_pool_bind(bs_ctx* c, int n_prompts, int n_rollouts, const int32_t* pool_tokens,
+                       const int64_t* rollout_offsets, const int32_t* prompt_rollout_begin) {
+  if (!c) return BS_EINVAL;
+  if (n_prompts < 1 || n_rollouts < 0 || !pool_tokens || !rollout_offsets || !prompt_rollout_begin)
+    return fail(c, BS_EINVAL, "bs_pool_bind: null pointer or bad count");
+  c->n_prompts = n_prompts;
+  c->n_rollouts = n_rollouts;
+  c->pool_tokens = pool_tokens;
+  c->rollout_offsets = rollout_offsets;
+  c->prompt_rollout_begin = prompt_rollout_begin;
+  return BS_OK;
+}
+
+bs_status bs_draft_lookup(bs_ctx* c, int B, const int32_t* seq_prompt, const int32_t* tail_tokens, int max_match,
+                          int min_match, int k_max, int32_t* draft_tokens, int32_t* draft_len, void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!c->pool_tokens) return fail(c, BS_ESTATE, "bs_draft_lookup: no pool bound");
+  if (!seq_prompt || !tail_tokens || !draft_tokens || !draft_len) return fail(c, BS_EINVAL, "bs_draft_lookup: null pointer");
+  if (B < 1 || B > c->B_max || k_max < 0 || k_max > c->k_max || max_match < 1 || max_match > 8 || min_match < 1 ||
+      min_match > max_match)
+    return fail(c, BS_ESHAPE, "bs_draft_lookup: B, k_max or match lengths out of range");
+  launch_lookup(B, c->n_prompts, c->pool_tokens, c->rollout_offsets, c->prompt_rollout_begin, seq_prompt, tail_tokens,
+                max_match, min_match, k_max, draft_tokens, draft_len, (hipStream_t)stream);
+  return check_hip(c);
+}
+
+bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_t* last_token,
+                         const int32_t* draft_tokens, const int32_t* draft_len, int k_max, float* logits_debug,
+                         void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!seq_slot || !last_token || !draft_len || (k_max > 0 && !draft_tokens))
+    return fail(c, BS_EINVAL, "bs_verify_step: null pointer");
+  if (B < 1 || B > c->B_max || k_max < 0 || k_max > c->k_max)
+    return fail(c, BS_ESHAPE, "bs_verify_step: B or k_max exceeds the context's limits");
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = c->s;
+  const int M_max = B * (k_max + 1);
+  const Plan& p = c->plan;
+  launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, st);
+  launch_embed(s, p, M_max, c->embed, c->h, st);
+  for (int l = 0; l < s.L; ++l) {
+    launch_rmsnorm(s, p, M_max, c->h, c->attn_norm[l], c->a, st);
+    launch_gemm(s.dtype, EPI_STORE, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st);
+    launch_rope_append(s, p, c->kv, M_max, c->qkv, c->k_pages[l], c->v_pages[l], st);
+    launch_attention(s, p, c->kv, B, k_max, M_max, c->qkv, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch, st);
+    launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l], c->h, st);
+    launch_rmsnorm(s, p, M_max, c->h, c->mlp_norm[l], c->a, st);
+    launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st);
+    launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l], c->h, st);
+  }
+  launch_rmsnorm(s, p, M_max, c->h, c->final_norm, c->hf, st);
+  if (logits_debug && s.dtype == BS_F32)
+    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, logits_debug, st);
+  if (logits_debug && s.dtype == BS_BF16) {
+    // same kernel and loop order as the fused path of bs_accept_resample, so the values are identical
+    launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, 1.0f, c->sb, logits_debug, st);
+  }
+  c->verify_pending = true;
+  c->last_B = B;
+  c->last_k_max = k_max;
+  return check_hip(c);
+}
+
+static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logits, const int32_t* draft_tokens,
+                               const int32_t* draft_len, int k_max, const void* q_logits, int q_dtype, float temperature,
+                               int eos_id, int emit_bonus, const float* u_accept, const float* u_sample,
+                               int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
+                               hipStream_t st) {
+  const Shape& s = c->s;
+  const Plan& p = c->plan;
+  const int M_max = B * (k_max + 1);
+  const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
+  const float* sample_base;
+  bool rows_selected = false;
+  int n_vtiles;
+  if (given_logits) {
+    launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, st);
+    launch_logit_stats(p, M_max, V, given_logits, inv_temp, c->sb, st);
+    n_vtiles = (V + 1023) / 1024;
+    sample_base = given_logits;
+  } else if (s.dtype == BS_F32) {
+    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, c->full_logits, st);
+    launch_logit_stats(p, M_max, V, c->full_logits, inv_temp, c->sb, st);
+    n_vtiles = (V + 1023) / 1024;
+    sample_base = c->full_logits;
+  } else {
+    launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, inv_temp, c->sb, nullptr, st);
+    n_vtiles = (V + 63) / 64;
+    sample_base = c->sb.sel_logits;
+    rows_selected = true;
+  }
+  if (q_logits) launch_q_stats(p, M_max, V, q_logits, q_dtype, c->sb, st);
+  launch_accept_scan(p, B, k_max, M_max, n_vtiles, q_logits != nullptr, temperature, eos_id, emit_bonus, u_accept, c->sb,
+                     n_accepted, out_tokens, n_emitted, near_tie, st);
+  if (temperature > 0.f) {
+    if (rows_selected) launch_lmhead_rows(s, B, c->hf, c->lm_head, c->sb, st);
+    launch_sample(B, k_max, V, sample_base, rows_selected, q_logits, q_dtype, temperature, u_sample, c->sb, n_accepted,
+                  out_tokens, n_emitted, near_tie, st);
+  }
+  return check_hip(c);
+}
+
+static bs_status check_accept_args(bs_ctx* c, int B, const int32_t* draft_tokens, const int32_t* draft_len, int k_max,
+                                   const void* q_logits, int q_dtype, float temperature, const float* u_accept,
+                                   const float* u_sample, int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted,
+                                   uint32_t* near_tie) {
+  if (!draft_len || (k_max > 0 && (!draft_tokens || !u_accept)) || !u_sample || !n_accepted || !out_tokens ||
+      !n_emitted || !near_tie)
+    return fail(c, BS_EINVAL, "accept_resample: null pointer");
+  if (!(temperature >= 0.f)) return fail(c, BS_EINVAL, "accept_resample: temperature must be >= 0");
+  if (q_logits && q_dtype != BS_F32 && q_dtype != BS_BF16) return fail(c, BS_EINVAL, "accept_resample: bad q_dtype");
+  if (B < 1 || B > c->B_max || k_max < 0 || k_max > c->k_max)
+    return fail(c, BS_ESHAPE, "accept_resample: B or k_max exceeds the context's limits");
+  return BS_OK;
+}
+
+bs_status bs_accept_resample(bs_ctx* c, int B, const int32_t* draft_tokens, const int32_t* draft_len, int k_max,
+                             const void* q_logits, int q_dtype, float temperature, int eos_id, int emit_bonus,
+                             const float* u_accept, const float* u_sample, int32_t* n_accepted, int32_t* out_tokens,
+                             int32_t* n_emitted, uint32_t* near_tie, void* stream) {
+  if (!c) return BS_EINVAL;
+  bs_status st = check_accept_args(c, B, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature, u_accept,
+                                   u_sample, n_accepted, out_tokens, n_emitted, near_tie);
+  if (st != BS_OK) return st;
+  if (!c->verify_pending) return fail(c, BS_ESTATE, "bs_accept_resample: no verify step pending");
+  if (B != c->last_B || k_max != c->last_k_max)
+    return fail(c, BS_ESHAPE, "bs_accept_resample: B / k_max differ from the verify step");
+  return accept_common(c, B, c->s.V, nullptr, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature, eos_id,
+                       emit_bonus, u_accept, u_sample, n_accepted, out_tokens, n_emitted, near_tie, (hipStream_t)stream);
+}
+
+bs_status bs_accept_resample_logits(bs_ctx* c, int B, int vocab, const float* logits, const int32_t* draft_tokens,
+                                    const int32_t* draft_len, int k_max, const void* q_logits, int q_dtype,
+                                    float temperature, int eos_id, int emit_bonus, const float* u_accept,
+                                    const float* u_sample, int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted,
+                                    uint32_t* near_tie, void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!logits) return fail(c, BS_EINVAL, "bs_accept_resample_logits: null logits");
+  if (vocab < 2 || vocab > c->s.V) return fail(c, BS_ESHAPE, "bs_accept_resample_logits: vocab outside [2, model vocab]");
+  bs_status st = check_accept_args(c, B, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature, u_accept,
+                                   u_sample, n_accepted, out_tokens, n_emitted, near_tie);
+  if (st != BS_OK) return st;
+  c->verify_pending = false;      // the plan in the workspace now describes this call, not a verify step
+  return accept_common(c, B, vocab, logits, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature, eos_id,
+                       emit_bonus, u_accept, u_sample, n_accepted, out_tokens, n_emitted, near_tie, (hipStream_t)stream);
+}
+
+bs_status bs_kv_commit(bs_ctx* c, int B, const int32_t* seq_slot, const int32_t* n_commit, void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!seq_slot || !n_commit) return fail(c, BS_EINVAL, "bs_kv_commit: null pointer");
+  if (!c->verify_pending) return fail(c, BS_ESTATE, "bs_kv_commit: no verify step pending");
+  if (B != c->last_B) return fail(c, BS_ESHAPE, "bs_kv_commit: B differs from the verify step");
+  launch_commit(c->plan, c->kv, B, seq_slot, n_commit, (hipStream_t)stream);
+  c->verify_pending = false;
+  return check_hip(c);
+}
+
+static bs_status kv_copy(bs_ctx* c, int layer, int slot, int pos0, int n, void* k_rows, void* v_rows, bool to_pages,
+                         void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!k_rows || !v_rows) return fail(c, BS_EINVAL, "bs_kv_write/read: null pointer");
+  if (layer < 0 || layer >= c->s.L || slot < 0 || slot >= c->kv.n_slots || pos0 < 0 || n < 0)
+    return fail(c, BS_ESHAPE, "bs_kv_write/read: layer, slot or range out of bounds");
+  if ((long)pos0 + n > (long)c->kv.max_pages * kPage) return fail(c, BS_ECAPACITY, "bs_kv_write/read: beyond the slot's pages");
+  launch_kv_copy(c->s, c->kv, slot, pos0, n, c->k_pages[layer], c->v_pages[layer], k_rows, v_rows, to_pages,
+                 (hipStream_t)stream);
+  return check_hip(c);
+}
+
+bs_status bs_kv_write(bs_ctx* c, int layer, int slot, int pos0, int n, const void* k_rows, const void* v_rows,
+                      void* stream) {
+  return kv_copy(c, layer, slot, pos0, n, (void*)k_rows, (void*)v_rows, true, stream);
+}
+bs_status bs_kv_read(bs_ctx* c, int layer, int slot, int pos0, int n, void* k_rows, void* v_rows, void* stream) {
+  return kv_copy(c, layer, slot, pos0, n, k_rows, v_rows, false, stream);
+}
+
+bs_status bs_poll_status(bs_ctx* c, void* stream, int32_t* fault_out) {
+  if (!c || !fault_out) return BS_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t host = 0;
+  if (hipMemcpyAsync(&host, c->plan.status, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return check_hip(c) == BS_OK ? fail(c, BS_EHIP, "bs_poll_status: copy failed") : BS_EHIP;
+  launch_clear_status(c->plan.status, st);
+  *fault_out = host;
+  return check_hip(c);
+}
+
+}  // extern "C"

@@ -1,0 +1,142 @@
+// Internal declarations shared by the translation units of libbubblespec (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/bubblespec.h"
+
+typedef __bf16 bf16;
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // RNE
+
+constexpr int kPage = BS_PAGE_TOKENS;   // tokens per KV page
+constexpr int kTile = 32;               // tokens per MFMA tile inside a page (bf16 layout)
+
+// ---------------------------------------------------------------------------------------------
+// Element order inside one KV page (all heads of one layer, kPage tokens).
+//
+// float32 pages are row-major [head][token][d] for both K and V.
+//
+// bfloat16 pages are stored in the operand order of the 32x32x16 bf16 MFMA so that the attention
+// kernel's wave-wide 16-byte-per-lane loads are 1 KiB contiguous and feed the matrix unit with no
+// LDS staging and no shuffles.  Per head a page is two tiles of 32 tokens.
+//   K tile: S^T = K Q^T uses K as the A operand.  A-row m of the tile holds token
+//           tau = 16*(m%8/4) + 4*(m/8) + m%4  (so that accumulator register i of lane group g
+//           is token 16g+i), and lane (m, g) needs, at K-step s, d = g*D/2 + 8s + j (j = 0..7;
+//           the contraction index may be permuted freely as long as Q uses the same order).
+//   V tile: O^T = V^T P^T uses V^T as the A operand, 32 d-values per d-tile; lane (d%32, g) at
+//           step t needs tokens 16g + 8t + j.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ size_t kv_page_elems(int Hkv, int D) { return (size_t)Hkv * kPage * D; }
+
+__host__ __device__ __forceinline__ int k_index_f32(int D, int h, int tok, int d) { return (h * kPage + tok) * D + d; }
+__host__ __device__ __forceinline__ int v_index_f32(int D, int h, int tok, int d) { return (h * kPage + tok) * D + d; }
+
+__host__ __device__ __forceinline__ int k_tile_row(int tau) {   // token in tile -> A-row m
+  return 4 * (tau / 16) + (tau % 4) + 8 * ((tau % 16) / 4);
+}
+__host__ __device__ __forceinline__ int k_index_bf16(int D, int h, int tok, int d) {
+  int tile = tok / kTile, m = k_tile_row(tok % kTile);
+  int g = d / (D / 2), r = d % (D / 2), s = r / 8, j = r % 8;
+  return ((((h * 2 + tile) * (D / 16) + s) * 2 + g) * 32 + m) * 8 + j;
+}
+__host__ __device__ __forceinline__ int v_index_bf16(int D, int h, int tok, int d) {
+  int tile = tok / kTile, tau = tok % kTile;
+  int g = tau / 16, t = (tau % 16) / 8, j = tau % 8, dt = d / 32, dl = d % 32;
+  return ((((((h * 2 + tile) * (D / 32) + dt) * 2 + t) * 2 + g) * 32 + dl) * 8) + j;
+}
+template <typename T> __host__ __device__ __forceinline__ int k_index(int D, int h, int tok, int d);
+template <> __host__ __device__ __forceinline__ int k_index<float>(int D, int h, int tok, int d) { return k_index_f32(D, h, tok, d); }
+template <> __host__ __device__ __forceinline__ int k_index<bf16>(int D, int h, int tok, int d) { return k_index_bf16(D, h, tok, d); }
+template <typename T> __host__ __device__ __forceinline__ int v_index(int D, int h, int tok, int d);
+template <> __host__ __device__ __forceinline__ int v_index<float>(int D, int h, int tok, int d) { return v_index_f32(D, h, tok, d); }
+template <> __host__ __device__ __forceinline__ int v_index<bf16>(int D, int h, int tok, int d) { return v_index_bf16(D, h, tok, d); }
+
+// ---------------------------------------------------------------------------------------------
+// Device-side plan of one step (lives in the workspace; written by plan_kernel).
+// ---------------------------------------------------------------------------------------------
+struct Plan {
+  int32_t* status;      // [1]   BS_FAULT_* bits (sticky until polled)
+  int32_t* n_rows;      // [2]   M, T_d
+  int32_t* row_start;   // [B+1] first packed row of sequence b (k_b+1 rows each)
+  int32_t* draft_start; // [B+1] first packed draft row of sequence b (k_b rows each)
+  int32_t* seq_k;       // [B]   validated k_b (-1: sequence skipped)
+  int32_t* seq_c;       // [B]   committed length c_b
+  int32_t* seq_slot;    // [B]   validated slot
+  int32_t* row_seq;     // [M_max] sequence of packed row r
+  int32_t* row_pos;     // [M_max] i in 0..k_b
+  int32_t* row_tok;     // [M_max] input token of row r
+  int32_t* row_target;  // [M_max] draft token judged by row r (-1: none)
+};
+
+struct KvView {
+  int n_pages, n_slots, max_pages;
+  const int32_t* block_table;
+  int32_t* ctx_len;
+};
+
+struct Shape {
+  int L, d, Hq, Hkv, D, F, V, dtype;
+  float eps, theta;
+  int Nqkv() const { return (Hq + 2 * Hkv) * D; }
+};
+
+// ---- launchers (each .hip file defines its own kernels and these host wrappers) ---------------
+// plan.hip
+void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, const int32_t* seq_slot,
+                 const int32_t* last_token, const int32_t* draft_tokens, const int32_t* draft_len,
+                 bool need_kv, hipStream_t st);
+void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot,
+                   const int32_t* n_commit, hipStream_t st);
+void launch_clear_status(int32_t* status, hipStream_t st);
+// elementwise.hip
+void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, hipStream_t st);
+void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, const float* gain, void* out,
+                    hipStream_t st);
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, void* qkv, void* k_pages,
+                        void* v_pages, hipStream_t st);
+void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
+                    void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
+// gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3 };
+void launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
+                 const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
+                 hipStream_t st);
+// attention.hip
+void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* qkv,
+                      const void* k_pages, const void* v_pages, void* out, void* scratch, hipStream_t st);
+size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
+// sampler.hip
+struct SamplerBufs {
+  float* part_max; float* part_sum; int32_t* part_arg;   // [n_vtiles, M_max]
+  float* z_target;                                       // [M_max] logit of the judged draft token
+  float* q_lse; float* q_target;                         // [M_max] per query row that judges a draft
+  int32_t* sel_row; int32_t* sel_mode; int32_t* sel_qrow; int32_t* sel_tok; // [B_max]
+  float* sel_logits;                                     // [B_max, V]
+};
+int lmhead_vtiles(int V);
+void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head,
+                         float inv_temp, const SamplerBufs& sb, float* logits_debug, hipStream_t st);
+void launch_logit_stats(const Plan& p, int M_max, int V, const float* logits, float inv_temp,
+                        const SamplerBufs& sb, hipStream_t st);
+void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_head, const SamplerBufs& sb,
+                        hipStream_t st);
+void launch_q_stats(const Plan& p, int M_max, int V, const void* q_logits, int q_dtype, const SamplerBufs& sb,
+                    hipStream_t st);
+void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles, bool dense_q, float temperature,
+                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
+                        int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st);
+void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
+                   int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
+                   const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
+                   hipStream_t st);
+// lookup.hip
+void launch_lookup(int B, int n_prompts, const int32_t* pool_tokens, const int64_t* rollout_offsets,
+                   const int32_t* prompt_rollout_begin, const int32_t* seq_prompt, const int32_t* tail,
+                   int max_match, int min_match, int k_max, int32_t* draft_tokens, int32_t* draft_len,
+                   hipStream_t st);

@@ -1,0 +1,108 @@
+// Device-side planning of one verify step, KV commit, status word.
+//
+// draft_len may be produced on the device by the lookup kernel, so the packing of the ragged
+// query rows (Alg. 1: every sequence verifies its own block of k_b drafts; Sec. 3.3: all query
+// lengths ride in one batch) is computed here, on the device, with no host round trip.
+#include "common.h"
+
+__global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int k_max, int vocab,
+                                                   const int32_t* __restrict__ seq_slot,
+                                                   const int32_t* __restrict__ last_token,
+                                                   const int32_t* __restrict__ draft_tokens,
+                                                   const int32_t* __restrict__ draft_len, int need_kv) {
+  __shared__ int s_fault;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_fault = 0;
+  __syncthreads();
+  // phase 1: per-sequence validation (parallel over sequences)
+  for (int b = tid; b < B; b += blockDim.x) {
+    int k = draft_len[b], fault = 0, c = 0, slot = 0;
+    if (k < 0 || k > k_max) { fault |= BS_FAULT_DRAFT_LEN; }
+    if (need_kv) {
+      slot = seq_slot[b];
+      if (slot < 0 || slot >= kv.n_slots) {
+        fault |= BS_FAULT_SLOT;
+      } else {
+        for (int b2 = 0; b2 < b; ++b2) if (seq_slot[b2] == slot) fault |= BS_FAULT_SLOT;
+        c = kv.ctx_len[slot];
+        if (!(fault & BS_FAULT_DRAFT_LEN)) {
+          if (c < 0 || (long)c + k + 1 > (long)kv.max_pages * kPage) {
+            fault |= BS_FAULT_KV_PAGES;
+          } else {
+            for (int pg = 0; pg <= (c + k) / kPage; ++pg) {
+              int id = kv.block_table[(size_t)slot * kv.max_pages + pg];
+              if (id < 0 || id >= kv.n_pages) fault |= BS_FAULT_KV_PAGES;
+            }
+          }
+        }
+      }
+    }
+    p.seq_k[b] = fault ? -1 : k;
+    p.seq_c[b] = c;
+    p.seq_slot[b] = slot;
+    if (fault) atomicOr(&s_fault, fault);
+  }
+  __syncthreads();
+  // phase 2: prefix sums (B is small; one thread)
+  if (tid == 0) {
+    int r = 0, t = 0;
+    for (int b = 0; b < B; ++b) {
+      p.row_start[b] = r;
+      p.draft_start[b] = t;
+      int k = p.seq_k[b];
+      if (k >= 0) { r += k + 1; t += k; }
+    }
+    p.row_start[B] = r;
+    p.draft_start[B] = t;
+    p.n_rows[0] = r;
+    p.n_rows[1] = t;
+  }
+  __syncthreads();
+  // phase 3: per-row maps (parallel over sequences x positions)
+  for (int idx = tid; idx < B * (k_max + 1); idx += blockDim.x) {
+    int b = idx / (k_max + 1), i = idx % (k_max + 1);
+    int k = p.seq_k[b];
+    if (k < 0 || i > k) continue;
+    int r = p.row_start[b] + i;
+    int tok = (i == 0) ? (last_token ? last_token[b] : 0) : draft_tokens[(size_t)b * k_max + i - 1];
+    if (tok < 0 || tok >= vocab) { atomicOr(&s_fault, BS_FAULT_TOKEN_ID); tok = 0; }
+    int tgt = -1;
+    if (i < k) {
+      tgt = draft_tokens[(size_t)b * k_max + i];
+      if (tgt < 0 || tgt >= vocab) tgt = 0;   // flagged when seen as an input token of row i+1
+    }
+    p.row_seq[r] = b;
+    p.row_pos[r] = i;
+    p.row_tok[r] = tok;
+    p.row_target[r] = tgt;
+  }
+  __syncthreads();
+  if (tid == 0 && s_fault) atomicOr(p.status, s_fault);
+}
+
+__global__ void commit_kernel(Plan p, KvView kv, int B, const int32_t* __restrict__ seq_slot,
+                              const int32_t* __restrict__ n_commit) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int k = p.seq_k[b];
+  if (k < 0) return;                       // sequence was skipped by the verify step
+  int n = n_commit[b];
+  if (n < 0 || n > k + 1 || seq_slot[b] != p.seq_slot[b]) { atomicOr(p.status, BS_FAULT_COMMIT); return; }
+  kv.ctx_len[p.seq_slot[b]] = p.seq_c[b] + n;
+}
+
+__global__ void clear_status_kernel(int32_t* status) { *status = 0; }
+
+void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, const int32_t* seq_slot,
+                 const int32_t* last_token, const int32_t* draft_tokens, const int32_t* draft_len,
+                 bool need_kv, hipStream_t st) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, p, kv, B, k_max, vocab, seq_slot, last_token,
+                     draft_tokens, draft_len, need_kv ? 1 : 0);
+}
+void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot, const int32_t* n_commit,
+                   hipStream_t st) {
+  hipLaunchKernelGGL(commit_kernel, dim3((B + 255) / 256), dim3(256), 0, st, p, kv, B, seq_slot, n_commit);
+}
+void launch_clear_status(int32_t* status, hipStream_t st) {
+  hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+}

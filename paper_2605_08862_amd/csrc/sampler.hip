@@ -1,0 +1,456 @@
+// LM head fused with softmax statistics, the accept scan of Alg. 1 and the residual / bonus
+// sampling of Eq. 2-3.  The [M, V] probabilities are never formed in HBM:
+//   phase 1  LM-head GEMM over all M rows whose epilogue keeps, per (row, vocabulary tile), only
+//            (max, sum exp, arg max) of z/T and the logit of the draft token judged by the row;
+//   scan     per sequence, the first rejected draft (Eq. 2, general form min(1, p/q));
+//   phase 2  the one row per sequence that is sampled from (recovered, bonus or plain token) is
+//            recomputed by the same MFMA loop (bit-identical logits) and sampled by inverse CDF in
+//            vocabulary order with float64 running sums (Eq. 3 / max(0, p - q)).
+#include "gemm_mfma.h"
+
+enum { MODE_NONE = 0, MODE_PLAIN = 1, MODE_RESID_ONEHOT = 2, MODE_RESID_DENSE = 3 };
+
+constexpr int kLmMT = 4, kLmNT = 2;                 // LM-head wave tile: 128 rows x 64 vocab entries
+constexpr int kLmVtile = kLmNT * 32;                // vocab entries per statistics tile (bf16 path)
+constexpr int kRowVtile = 1024;                     // vocab entries per statistics tile (logits path)
+
+int lmhead_vtiles(int V) {
+  int a = (V + kLmVtile - 1) / kLmVtile, b = (V + kRowVtile - 1) / kRowVtile;
+  return a > b ? a : b;
+}
+
+// ------------------------------------------------------------------ phase 1 / phase 2 GEMM (bf16)
+// STATS = true : rows are the packed query rows; epilogue writes statistics (+ optional debug logits).
+// STATS = false: rows are gathered through sel_row (one per sequence); epilogue stores float32 logits
+//                to sel_logits [B, V].
+template <bool STATS>
+__global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int V, int K,
+                                                     const bf16* __restrict__ X, const int32_t* __restrict__ x_rows,
+                                                     const bf16* __restrict__ W, float inv_temp,
+                                                     const int32_t* __restrict__ row_target, SamplerBufs sb,
+                                                     float* __restrict__ store, int m_blocks, int n_blocks) {
+  using G = MfmaGemm<kLmMT, kLmNT, true>;
+  extern __shared__ __align__(16) char lds[];
+  const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
+  const int total = m_blocks * n_blocks;
+  const int per_xcd = (total + 7) / 8;
+  const int id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (id >= total) return;
+  const int mb = id % m_blocks, nb = id / m_blocks;
+  const int m0 = mb * G::BM;
+  if (m0 >= M) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int vt = nb * 4 + wave;                       // statistics tile of this wave
+  const int n_wave0 = vt * kLmVtile;
+
+  const bf16* x_ptr[kLmMT];
+  int x_lds[kLmMT];
+#pragma unroll
+  for (int i = 0; i < kLmMT; ++i) {
+    int row, g, s;
+    G::chunk_of(i, row, g, s);
+    int r = min(m0 + row, M - 1);
+    if (x_rows) r = x_rows[r];
+    x_ptr[i] = X + (size_t)r * K + g * 32 + s * 8;
+    x_lds[i] = G::chunk_lds_offset(row, g, s);
+  }
+  const bf16* w_ptr[kLmNT];
+#pragma unroll
+  for (int ni = 0; ni < kLmNT; ++ni) {
+    int n = min(n_wave0 + ni * 32 + (lane & 31), V - 1);
+    w_ptr[ni] = W + (size_t)n * K + (lane >> 5) * 32;
+  }
+  f32x16 acc[kLmMT][kLmNT];
+#pragma unroll
+  for (int mi = 0; mi < kLmMT; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+  G::run(acc, x_ptr, x_lds, w_ptr, K / kBK, lds);
+  if (n_wave0 >= V) return;
+
+  // accumulator (SWAP): rows = vocabulary entries n_wave0 + ni*32 + acc_row, lane column = token
+#pragma unroll
+  for (int mi = 0; mi < kLmMT; ++mi) {
+    const int m = m0 + mi * 32 + acc_col(lane);
+    const bool valid = m < M;
+    if (STATS) {
+      const int tgt = valid ? row_target[m] : -1;
+      float mx = -INFINITY;
+      int arg = 0x7fffffff;
+#pragma unroll
+      for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = n_wave0 + ni * 32 + acc_row(lane, i);
+          const float z = acc[mi][ni][i];
+          if (n < V) {
+            if (z > mx) { mx = z; arg = n; }
+            if (valid && n == tgt) sb.z_target[m] = z;
+            if (valid && store) store[(size_t)m * V + n] = z;
+          }
+        }
+      const float mx_o = __shfl_xor(mx, 32);
+      const int arg_o = __shfl_xor(arg, 32);
+      if (mx_o > mx || (mx_o == mx && arg_o < arg)) { mx = mx_o; arg = arg_o; }
+      float sum = 0.f;
+#pragma unroll
+      for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = n_wave0 + ni * 32 + acc_row(lane, i);
+          if (n < V) sum += __expf((acc[mi][ni][i] - mx) * inv_temp);
+        }
+      sum += __shfl_xor(sum, 32);
+      if (valid && lane < 32) {
+        const size_t o = (size_t)vt * M_max + m;
+        sb.part_max[o] = mx;
+        sb.part_sum[o] = sum;
+        sb.part_arg[o] = arg;
+      }
+    } else {
+      if (!valid) continue;
+#pragma unroll
+      for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = n_wave0 + ni * 32 + acc_row(lane, i);
+          if (n < V) store[(size_t)m * V + n] = acc[mi][ni][i];
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ statistics of given float32 logits
+__global__ void __launch_bounds__(256) logit_stats_kernel(Plan p, int M_max, int V, const float* __restrict__ logits,
+                                                          float inv_temp, SamplerBufs sb) {
+  __shared__ float s_mx[4], s_sum[4];
+  __shared__ int s_arg[4];
+  const int m = blockIdx.y, vt = blockIdx.x;
+  if (m >= p.n_rows[0]) return;
+  const int tgt = p.row_target[m];
+  const float* z = logits + (size_t)m * V;
+  const int base = vt * kRowVtile;
+  float v[4];
+  float mx = -INFINITY;
+  int arg = 0x7fffffff;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int n = base + j * 256 + threadIdx.x;
+    v[j] = (n < V) ? z[n] : -INFINITY;
+    if (n < V && n == tgt) sb.z_target[m] = v[j];
+    if (v[j] > mx) { mx = v[j]; arg = n; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    float mo = __shfl_xor(mx, o);
+    int ao = __shfl_xor(arg, o);
+    if (mo > mx || (mo == mx && ao < arg)) { mx = mo; arg = ao; }
+  }
+  if ((threadIdx.x & 63) == 0) { s_mx[threadIdx.x >> 6] = mx; s_arg[threadIdx.x >> 6] = arg; }
+  __syncthreads();
+  mx = s_mx[0]; arg = s_arg[0];
+  for (int w = 1; w < 4; ++w)
+    if (s_mx[w] > mx || (s_mx[w] == mx && s_arg[w] < arg)) { mx = s_mx[w]; arg = s_arg[w]; }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) sum += (v[j] == -INFINITY) ? 0.f : __expf((v[j] - mx) * inv_temp);
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const size_t o = (size_t)vt * M_max + m;
+    sb.part_max[o] = mx;
+    sb.part_sum[o] = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+    sb.part_arg[o] = arg;
+  }
+}
+
+// ------------------------------------------------------------------ proposal statistics
+// For every query row that judges a draft: log-sum-exp of its q_logits row and q_logits[draft].
+template <typename Q>
+__global__ void __launch_bounds__(256) q_stats_kernel(Plan p, int V, const Q* __restrict__ q_logits, SamplerBufs sb) {
+  __shared__ float s_red[4];
+  const int r = blockIdx.x;
+  if (r >= p.n_rows[0]) return;
+  const int tgt = p.row_target[r];
+  if (tgt < 0) return;
+  const int b = p.row_seq[r];
+  const Q* q = q_logits + (size_t)(p.draft_start[b] + p.row_pos[r]) * V;
+  float mx = -INFINITY;
+  for (int n = threadIdx.x; n < V; n += 256) mx = fmaxf(mx, to_f32<Q>(q[n]));
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int n = threadIdx.x; n < V; n += 256) sum += __expf(to_f32<Q>(q[n]) - mx);
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    sb.q_lse[r] = mx + logf(s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+    sb.q_target[r] = to_f32<Q>(q[tgt]);
+  }
+}
+
+// ------------------------------------------------------------------ accept scan (Alg. 1 inner loop, Eq. 2)
+__global__ void __launch_bounds__(256) accept_scan_kernel(Plan p, int k_max, int M_max, int n_vtiles, int dense_q,
+                                                          float temperature, int eos_id, int emit_bonus,
+                                                          const float* __restrict__ u_accept, SamplerBufs sb,
+                                                          int32_t* __restrict__ n_accepted,
+                                                          int32_t* __restrict__ out_tokens,
+                                                          int32_t* __restrict__ n_emitted,
+                                                          uint32_t* __restrict__ near_tie) {
+  __shared__ float s_mx[4], s_sum[4];
+  __shared__ int s_arg[4];
+  __shared__ float s_lse[BS_MAX_K + 1];
+  __shared__ int s_argmax[BS_MAX_K + 1];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int k = p.seq_k[b];
+  int32_t* out = out_tokens + (size_t)b * (k_max + 1);
+  if (k < 0) {                                      // sequence skipped by the plan
+    if (tid == 0) { n_accepted[b] = 0; n_emitted[b] = 0; near_tie[b] = 0; sb.sel_mode[b] = MODE_NONE; sb.sel_row[b] = 0; }
+    for (int i = tid; i <= k_max; i += 256) out[i] = -1;
+    return;
+  }
+  const int r0 = p.row_start[b];
+  const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
+  for (int i = 0; i <= k; ++i) {                    // combine the per-tile statistics of row i
+    const int r = r0 + i;
+    float mx = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int vt = tid; vt < n_vtiles; vt += 256) {
+      float m2 = sb.part_max[(size_t)vt * M_max + r];
+      int a2 = sb.part_arg[(size_t)vt * M_max + r];
+      if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      float mo = __shfl_xor(mx, o);
+      int ao = __shfl_xor(arg, o);
+      if (mo > mx || (mo == mx && ao < arg)) { mx = mo; arg = ao; }
+    }
+    if ((tid & 63) == 0) { s_mx[tid >> 6] = mx; s_arg[tid >> 6] = arg; }
+    __syncthreads();
+    mx = s_mx[0]; arg = s_arg[0];
+    for (int w = 1; w < 4; ++w)
+      if (s_mx[w] > mx || (s_mx[w] == mx && s_arg[w] < arg)) { mx = s_mx[w]; arg = s_arg[w]; }
+    float sum = 0.f;
+    for (int vt = tid; vt < n_vtiles; vt += 256) {
+      float m2 = sb.part_max[(size_t)vt * M_max + r];
+      if (m2 > -INFINITY) sum += sb.part_sum[(size_t)vt * M_max + r] * __expf((m2 - mx) * inv_temp);
+    }
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
+    __syncthreads();
+    if (tid == 0) {
+      s_lse[i] = mx * inv_temp + logf(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
+      s_argmax[i] = arg;
+    }
+    __syncthreads();
+  }
+  if (tid != 0) return;
+  int n_acc = 0, mode = MODE_NONE, sel = r0, sel_tok = -1, n_out = 0;
+  uint32_t tie = 0;
+  bool stopped = false;
+  for (int i = 0; i < k && !stopped; ++i) {
+    const int r = r0 + i;
+    const int x = p.row_target[r];
+    float px;
+    if (temperature > 0.f) px = __expf(sb.z_target[r] * inv_temp - s_lse[i]);
+    else px = (x == s_argmax[i]) ? 1.0f : 0.0f;
+    float rho = px;
+    if (dense_q) {
+      float qx = __expf(sb.q_target[r] - sb.q_lse[r]);
+      rho = (qx == 0.f) ? INFINITY : px / qx;
+    }
+    const float u = u_accept[(size_t)b * k_max + i];
+    if (fabsf(rho - u) <= 1e-3f) tie |= 1u << i;
+    if (u < fminf(1.0f, rho)) {
+      out[n_out++] = x;
+      ++n_acc;
+      if (x == eos_id) stopped = true;
+    } else {
+      sel = r; sel_tok = x;
+      mode = dense_q ? MODE_RESID_DENSE : MODE_RESID_ONEHOT;
+      stopped = true;
+    }
+  }
+  if (mode == MODE_NONE && !(n_acc > 0 && out[n_acc - 1] == eos_id) && (emit_bonus || k == 0)) {
+    sel = r0 + k;
+    mode = MODE_PLAIN;
+  }
+  if (mode != MODE_NONE && temperature == 0.f) {    // one-hot target: every sampled token is the arg-max
+    out[n_out++] = s_argmax[sel - r0];
+    mode = MODE_NONE;
+  }
+  for (int i = n_out; i <= k_max; ++i) out[i] = -1;
+  n_accepted[b] = n_acc;
+  n_emitted[b] = n_out;
+  near_tie[b] = tie;
+  sb.sel_row[b] = sel;
+  sb.sel_mode[b] = mode;
+  sb.sel_tok[b] = sel_tok;
+  sb.sel_qrow[b] = p.draft_start[b] + (sel - r0);
+}
+
+// ------------------------------------------------------------------ inverse-CDF sampling (Eq. 3)
+// One workgroup of 1024 threads per sequence; thread t owns a contiguous slice of the vocabulary.
+template <typename Q>
+__global__ void __launch_bounds__(1024) sample_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
+                                                      const Q* __restrict__ q_logits, float temperature,
+                                                      const float* __restrict__ u_sample, SamplerBufs sb,
+                                                      const int32_t* __restrict__ n_accepted, int k_max,
+                                                      int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
+                                                      uint32_t* __restrict__ near_tie) {
+  __shared__ double s_d[16];
+  __shared__ double s_scan[1024];
+  __shared__ int s_i[2];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  int mode = sb.sel_mode[b];
+  if (mode == MODE_NONE) return;
+  const float* z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
+  const Q* q = (mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
+  const int tgt = sb.sel_tok[b];
+  const double T = (double)temperature;
+  const int chunk = (V + 1023) / 1024;
+  const int j0 = min(tid * chunk, V), j1 = min(j0 + chunk, V);
+
+  auto block_max = [&](double v) {
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+    __syncthreads();
+    if ((tid & 63) == 0) s_d[tid >> 6] = v;
+    __syncthreads();
+    double r = s_d[0];
+    for (int w = 1; w < 16; ++w) r = fmax(r, s_d[w]);
+    return r;
+  };
+  auto block_sum = [&](double v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((tid & 63) == 0) s_d[tid >> 6] = v;
+    __syncthreads();
+    double r = 0.0;
+    for (int w = 0; w < 16; ++w) r += s_d[w];
+    return r;
+  };
+
+  // pass A: normalisers of p (and q)
+  double mxp = -INFINITY, mxq = -INFINITY;
+  for (int j = j0; j < j1; ++j) {
+    mxp = fmax(mxp, (double)z[j] / T);
+    if (q) mxq = fmax(mxq, (double)to_f32<Q>(q[j]));
+  }
+  mxp = block_max(mxp);
+  if (q) mxq = block_max(mxq);
+  double sp = 0.0, sq = 0.0;
+  for (int j = j0; j < j1; ++j) {
+    sp += exp((double)z[j] / T - mxp);
+    if (q) sq += exp((double)to_f32<Q>(q[j]) - mxq);
+  }
+  sp = block_sum(sp);
+  if (q) sq = block_sum(sq);
+
+  auto weight = [&](int j) -> double {
+    double pj = exp((double)z[j] / T - mxp) / sp;
+    if (mode == MODE_PLAIN) return pj;
+    if (mode == MODE_RESID_ONEHOT) return j == tgt ? 0.0 : pj;
+    double qj = exp((double)to_f32<Q>(q[j]) - mxq) / sq;
+    return fmax(0.0, pj - qj);
+  };
+
+  double csum, total;
+  for (;;) {
+    // pass B: slice sums and their inclusive scan
+    csum = 0.0;
+    for (int j = j0; j < j1; ++j) csum += weight(j);
+    s_scan[tid] = csum;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      double v = (tid >= o) ? s_scan[tid - o] : 0.0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    total = s_scan[1023];
+    if (total > 0.0 || mode == MODE_PLAIN) break;
+    mode = MODE_PLAIN;                              // empty residual: fall back to the target itself
+    __syncthreads();
+  }
+  const double incl = s_scan[tid], excl = incl - csum;
+  const double t = (double)u_sample[b] * total;
+  if (tid == 0) { s_i[0] = 0x7fffffff; s_i[1] = -1; }
+  __syncthreads();
+  // owner = first slice whose inclusive sum exceeds t; fallback = last slice with weight
+  if (csum > 0.0) {
+    if (incl > t && excl <= t) atomicMin(&s_i[0], tid);
+    atomicMax(&s_i[1], tid);
+  }
+  __syncthreads();
+  const int owner = (s_i[0] != 0x7fffffff) ? s_i[0] : s_i[1];
+  if (tid != owner) return;
+  double run = excl, w = 0.0;
+  int tok = -1, last = -1;
+  double last_hi = 0.0, last_w = 0.0;
+  for (int j = j0; j < j1; ++j) {
+    w = weight(j);
+    run += w;
+    if (w > 0.0) { last = j; last_hi = run; last_w = w; }
+    if (run > t) { tok = j; break; }
+  }
+  if (tok < 0) { tok = last; run = last_hi; w = last_w; }
+  const int n_acc = n_accepted[b];
+  out_tokens[(size_t)b * (k_max + 1) + n_acc] = tok;
+  n_emitted[b] = n_acc + 1;
+  const double lo = run - w;
+  if (fmin(fabs(t - lo), fabs(run - t)) <= 1e-3 * w) near_tie[b] |= 0x80000000u;
+}
+
+// ------------------------------------------------------------------ launchers
+void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head, float inv_temp,
+                         const SamplerBufs& sb, float* logits_debug, hipStream_t st) {
+  using G = MfmaGemm<kLmMT, kLmNT, true>;
+  int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
+  int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
+  hipLaunchKernelGGL(lmhead_kernel<true>, dim3(grid), dim3(256), G::LDS_BYTES, st, p.n_rows, M_max, s.V, s.d,
+                     (const bf16*)hf, (const int32_t*)nullptr, (const bf16*)lm_head, inv_temp, p.row_target, sb,
+                     logits_debug, m_blocks, n_blocks);
+}
+void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_head, const SamplerBufs& sb,
+                        hipStream_t st) {
+  using G = MfmaGemm<kLmMT, kLmNT, true>;
+  int m_blocks = (B + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
+  int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
+  hipLaunchKernelGGL(lmhead_kernel<false>, dim3(grid), dim3(256), G::LDS_BYTES, st, (const int32_t*)nullptr, B, s.V, s.d,
+                     (const bf16*)hf, sb.sel_row, (const bf16*)lm_head, 1.0f, (const int32_t*)nullptr, sb,
+                     sb.sel_logits, m_blocks, n_blocks);
+}
+void launch_logit_stats(const Plan& p, int M_max, int V, const float* logits, float inv_temp, const SamplerBufs& sb,
+                        hipStream_t st) {
+  dim3 grid((V + kRowVtile - 1) / kRowVtile, M_max);
+  hipLaunchKernelGGL(logit_stats_kernel, grid, dim3(256), 0, st, p, M_max, V, logits, inv_temp, sb);
+}
+void launch_q_stats(const Plan& p, int M_max, int V, const void* q_logits, int q_dtype, const SamplerBufs& sb,
+                    hipStream_t st) {
+  if (q_dtype == BS_F32) hipLaunchKernelGGL(q_stats_kernel<float>, dim3(M_max), dim3(256), 0, st, p, V, (const float*)q_logits, sb);
+  else hipLaunchKernelGGL(q_stats_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, V, (const bf16*)q_logits, sb);
+}
+void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles, bool dense_q, float temperature,
+                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
+                        int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
+  hipLaunchKernelGGL(accept_scan_kernel, dim3(B), dim3(256), 0, st, p, k_max, M_max, n_vtiles, dense_q ? 1 : 0,
+                     temperature, eos_id, emit_bonus, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
+}
+void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
+                   int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
+                   const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
+                   hipStream_t st) {
+  if (temperature == 0.f) return;                    // the scan already emitted the arg-max tokens
+  if (q_logits && q_dtype == BS_BF16)
+    hipLaunchKernelGGL(sample_kernel<bf16>, dim3(B), dim3(1024), 0, st, V, logit_base, rows_are_selected ? 1 : 0,
+                       (const bf16*)q_logits, temperature, u_sample, sb, n_accepted, k_max, out_tokens, n_emitted, near_tie);
+  else
+    hipLaunchKernelGGL(sample_kernel<float>, dim3(B), dim3(1024), 0, st, V, logit_base, rows_are_selected ? 1 : 0,
+                       (const float*)q_logits, temperature, u_sample, sb, n_accepted, k_max, out_tokens, n_emitted, near_tie);
+}

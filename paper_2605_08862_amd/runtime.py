@@ -1,0 +1,130 @@
+"""Torch plumbing around the C ABI: device allocations (weights, paged KV cache, block table,
+workspace) and tensor-level wrappers of the step calls.  No arithmetic of the method lives here;
+every step runs in libbubblespec.so."""
+import torch
+
+from . import binding as B
+
+TORCH_DTYPE = {B.BS_F32: torch.float32, B.BS_BF16: torch.bfloat16}
+
+
+def fuse_weights(w, dtype, device):
+    """Layout marshalling: per-matrix weights (oracle naming: wq/wk/wv, w_gate/w_up, ...) as torch tensors
+    -> the fused row-major layout of bs_weights on `device`."""
+    td = TORCH_DTYPE[dtype]
+    dev = lambda t, dt=td: t.to(device=device, dtype=dt).contiguous()
+    out = {"embed": dev(w["embed"]), "lm_head": dev(w["lm_head"]), "final_norm": dev(w["final_norm"], torch.float32),
+           "attn_norm": [], "wqkv": [], "wo": [], "mlp_norm": [], "w_gate_up": [], "w_down": []}
+    for lw in w["layers"]:
+        out["attn_norm"].append(dev(lw["attn_norm"], torch.float32))
+        out["mlp_norm"].append(dev(lw["mlp_norm"], torch.float32))
+        out["wqkv"].append(torch.cat([dev(lw["wq"]), dev(lw["wk"]), dev(lw["wv"])], dim=0).contiguous())
+        out["wo"].append(dev(lw["wo"]))
+        out["w_gate_up"].append(torch.cat([dev(lw["w_gate"]), dev(lw["w_up"])], dim=0).contiguous())
+        out["w_down"].append(dev(lw["w_down"]))
+    return out
+
+
+class Engine:
+    """Owns the device buffers of one context and forwards to the C ABI."""
+
+    def __init__(self, desc, weights, n_slots, max_ctx, B_max, k_max, device="cuda:0", page_perm_seed=None):
+        self.desc = dict(desc)
+        self.device = torch.device(device)
+        self.cdesc = B.make_desc(desc)
+        self.B_max, self.k_max = B_max, k_max
+        self.weights = weights
+        td = TORCH_DTYPE[desc["dtype"]]
+        P = B.BS_PAGE_TOKENS
+        self.max_pages = (max_ctx + P - 1) // P
+        self.n_slots = n_slots
+        self.n_pages = n_slots * self.max_pages
+        page_elems = desc["n_kv_heads"] * P * desc["head_dim"]
+        # pages are zero-initialised: masked positions still enter the P*V product with weight 0
+        self.k_pages = [torch.zeros(self.n_pages, page_elems, dtype=td, device=self.device)
+                        for _ in range(desc["n_layers"])]
+        self.v_pages = [torch.zeros(self.n_pages, page_elems, dtype=td, device=self.device)
+                        for _ in range(desc["n_layers"])]
+        ids = torch.arange(self.n_pages, dtype=torch.int32)
+        if page_perm_seed is not None:      # scatter pages to exercise the block table
+            g = torch.Generator().manual_seed(page_perm_seed)
+            ids = ids[torch.randperm(self.n_pages, generator=g)]
+        self.block_table = ids.view(n_slots, self.max_pages).contiguous().to(self.device)
+        self.ctx_len = torch.zeros(n_slots, dtype=torch.int32, device=self.device)
+        nbytes = B.bs_workspace_bytes(self.cdesc, B_max, k_max)
+        if nbytes == 0:
+            raise B.BsError(B.BS_ESHAPE, "bs_workspace_bytes rejected the shape")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        kv = dict(n_pages=self.n_pages, n_slots=n_slots, max_pages_per_seq=self.max_pages, k_pages=self.k_pages,
+                  v_pages=self.v_pages, block_table=self.block_table, ctx_len=self.ctx_len)
+        self.ctx = B.bs_create(self.cdesc, weights, kv, self.workspace, B_max, k_max)
+        self._pool = None
+
+    def close(self):
+        if self.ctx is not None:
+            B.bs_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- draft database -----------------------------------------------------------------------
+    def pool_bind(self, pool_tokens, rollout_offsets, prompt_rollout_begin):
+        self._pool = (pool_tokens.to(self.device, torch.int32).contiguous(),
+                      rollout_offsets.to(self.device, torch.int64).contiguous(),
+                      prompt_rollout_begin.to(self.device, torch.int32).contiguous())
+        B.bs_pool_bind(self.ctx, self._pool[2].numel() - 1, self._pool[1].numel() - 1, *self._pool)
+
+    def draft_lookup(self, seq_prompt, tail_tokens, max_match, min_match, k_max):
+        n = seq_prompt.numel()
+        draft_tokens = torch.empty(n, max(k_max, 1), dtype=torch.int32, device=self.device)[:, :k_max].contiguous()
+        draft_len = torch.empty(n, dtype=torch.int32, device=self.device)
+        B.bs_draft_lookup(self.ctx, n, seq_prompt, tail_tokens, max_match, min_match, k_max, draft_tokens, draft_len)
+        return draft_tokens, draft_len
+
+    # -- step ---------------------------------------------------------------------------------
+    def verify_step(self, seq_slot, last_token, draft_tokens, draft_len, k_max, want_logits=False):
+        n = seq_slot.numel()
+        logits = None
+        if want_logits:
+            logits = torch.zeros(n * (k_max + 1), self.desc["vocab"], dtype=torch.float32, device=self.device)
+        B.bs_verify_step(self.ctx, n, seq_slot, last_token, draft_tokens, draft_len, k_max, logits)
+        return logits
+
+    def accept_resample(self, draft_tokens, draft_len, k_max, u_accept, u_sample, q_logits=None, temperature=1.0,
+                        eos_id=-1, emit_bonus=True, logits=None, vocab=None):
+        n = draft_len.numel()
+        out = dict(n_accepted=torch.empty(n, dtype=torch.int32, device=self.device),
+                   out_tokens=torch.empty(n, k_max + 1, dtype=torch.int32, device=self.device),
+                   n_emitted=torch.empty(n, dtype=torch.int32, device=self.device),
+                   near_tie=torch.empty(n, dtype=torch.int32, device=self.device))
+        q_dtype = B.BS_F32
+        if q_logits is not None:
+            q_dtype = B.BS_BF16 if q_logits.dtype == torch.bfloat16 else B.BS_F32
+        args = (draft_tokens, draft_len, k_max, q_logits, q_dtype, float(temperature), eos_id, emit_bonus, u_accept,
+                u_sample, out["n_accepted"], out["out_tokens"], out["n_emitted"], out["near_tie"])
+        if logits is None:
+            B.bs_accept_resample(self.ctx, n, *args)
+        else:
+            B.bs_accept_resample_logits(self.ctx, n, vocab if vocab is not None else logits.shape[1], logits, *args)
+        return out
+
+    def kv_commit(self, seq_slot, n_commit):
+        B.bs_kv_commit(self.ctx, seq_slot.numel(), seq_slot, n_commit)
+
+    def kv_write(self, layer, slot, pos0, k_rows, v_rows):
+        B.bs_kv_write(self.ctx, layer, slot, pos0, k_rows.shape[0], k_rows.contiguous(), v_rows.contiguous())
+
+    def kv_read(self, layer, slot, pos0, n):
+        td = TORCH_DTYPE[self.desc["dtype"]]
+        shape = (n, self.desc["n_kv_heads"], self.desc["head_dim"])
+        k = torch.empty(shape, dtype=td, device=self.device)
+        v = torch.empty(shape, dtype=td, device=self.device)
+        B.bs_kv_read(self.ctx, layer, slot, pos0, n, k, v)
+        return k, v
+
+    def poll_status(self):
+        return B.bs_poll_status(self.ctx)
