@@ -10,15 +10,18 @@ struct bs_ctx {
   KvView kv;
   int B_max, k_max, M_max;
   std::vector<const float*> attn_norm, mlp_norm;
-  std::vector<const void*> wqkv, wo, w_gate_up, w_down;
+  std::vector<const void*> wqkv, wo, w_gate_up, w_down;   // GEMM operands: raw (float32) or packed float16 copies
   std::vector<void*> k_pages, v_pages;
   const void *embed, *lm_head;
   const float* final_norm;
   // workspace
   Plan plan;
   float* h;            // residual stream  [M_max, d] float32
-  void* a;             // normed rows      [M_max, d]
-  void* qkv;           // [M_max, (Hq+2Hkv) D]
+  std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down;         // bf16 models: packed copies in the workspace
+  void* pk_lm = nullptr;
+  void* a;             // normed rows      [M_max, d] (GEMM operand type: float32 / float16)
+  float* qkv;          // [M_max, (Hq+2Hkv) D] float32 projection (rounded once, after the rotation)
+  void* q;             // [M_max, Hq D] rotated queries
   void* attn_out;      // [M_max, Hq D]
   void* act;           // [M_max, F]
   void* hf;            // final-norm rows  [M_max, d]
@@ -84,8 +87,9 @@ size_t carve(bs_ctx* c, char* base) {
   p.row_tok = w.take<int32_t>(M);
   p.row_target = w.take<int32_t>(M);
   c->h = w.take<float>((size_t)M * s.d);
-  c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));
-  c->qkv = w.take<char>((size_t)M * s.Nqkv() * elt(s.dtype));
+  c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
+  c->qkv = w.take<float>((size_t)M * s.Nqkv());
+  c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
   c->attn_out = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
   c->act = w.take<char>((size_t)M * s.F * elt(s.dtype));
   c->hf = w.take<char>((size_t)M * s.d * elt(s.dtype));
@@ -108,6 +112,14 @@ size_t carve(bs_ctx* c, char* base) {
   } else {
     c->full_logits = nullptr;
     sb.sel_logits = w.take<float>((size_t)B * s.V);
+    c->pk_qkv.assign(s.L, nullptr); c->pk_o.assign(s.L, nullptr); c->pk_gu.assign(s.L, nullptr); c->pk_down.assign(s.L, nullptr);
+    for (int l = 0; l < s.L; ++l) {
+      c->pk_qkv[l] = w.take<uint16_t>(packed_weight_elems(s.Nqkv(), s.d));
+      c->pk_o[l] = w.take<uint16_t>(packed_weight_elems(s.d, s.Hq * s.D));
+      c->pk_gu[l] = w.take<uint16_t>(packed_weight_elems(2 * s.F, s.d));
+      c->pk_down[l] = w.take<uint16_t>(packed_weight_elems(s.d, s.F));
+    }
+    c->pk_lm = w.take<uint16_t>(packed_weight_elems(s.V, s.d));
   }
   return (w.off + 255) & ~(size_t)255;
 }
@@ -167,15 +179,32 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
         !kv->k_pages[l] || !kv->v_pages[l]) { delete c; return BS_EINVAL; }
     c->attn_norm.push_back(w->attn_norm[l]);
     c->mlp_norm.push_back(w->mlp_norm[l]);
-    c->wqkv.push_back(w->wqkv[l]);
-    c->wo.push_back(w->wo[l]);
-    c->w_gate_up.push_back(w->w_gate_up[l]);
-    c->w_down.push_back(w->w_down[l]);
+    if (desc->dtype == BS_F32) {
+      c->wqkv.push_back(w->wqkv[l]);
+      c->wo.push_back(w->wo[l]);
+      c->w_gate_up.push_back(w->w_gate_up[l]);
+      c->w_down.push_back(w->w_down[l]);
+    } else {       // one-time re-pack into MFMA operand order (float16); the originals are not used afterwards
+      const Shape& s = c->s;
+      hipStream_t ps = (hipStream_t)stream;
+      launch_pack_weight(w->wqkv[l], s.Nqkv(), s.d, c->pk_qkv[l], ps);
+      launch_pack_weight(w->wo[l], s.d, s.Hq * s.D, c->pk_o[l], ps);
+      launch_pack_weight(w->w_gate_up[l], 2 * s.F, s.d, c->pk_gu[l], ps);
+      launch_pack_weight(w->w_down[l], s.d, s.F, c->pk_down[l], ps);
+      c->wqkv.push_back(c->pk_qkv[l]);
+      c->wo.push_back(c->pk_o[l]);
+      c->w_gate_up.push_back(c->pk_gu[l]);
+      c->w_down.push_back(c->pk_down[l]);
+    }
     c->k_pages.push_back(kv->k_pages[l]);
     c->v_pages.push_back(kv->v_pages[l]);
   }
   c->embed = w->embed;
   c->lm_head = w->lm_head;
+  if (desc->dtype == BS_BF16) {
+    launch_pack_weight(w->lm_head, desc->vocab, desc->d_model, c->pk_lm, (hipStream_t)stream);
+    c->lm_head = c->pk_lm;
+  }
   c->final_norm = w->final_norm;
   c->kv = KvView{kv->n_pages, kv->n_slots, kv->max_pages_per_seq, kv->block_table, kv->ctx_len};
   launch_clear_status(c->plan.status, (hipStream_t)stream);
@@ -231,9 +260,9 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   launch_embed(s, p, M_max, c->embed, c->h, st);
   for (int l = 0; l < s.L; ++l) {
     launch_rmsnorm(s, p, M_max, c->h, c->attn_norm[l], c->a, st);
-    launch_gemm(s.dtype, EPI_STORE, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st);
-    launch_rope_append(s, p, c->kv, M_max, c->qkv, c->k_pages[l], c->v_pages[l], st);
-    launch_attention(s, p, c->kv, B, k_max, M_max, c->qkv, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch, st);
+    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st);
+    launch_rope_append(s, p, c->kv, M_max, c->qkv, c->q, c->k_pages[l], c->v_pages[l], st);
+    launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch, st);
     launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l], c->h, st);
     launch_rmsnorm(s, p, M_max, c->h, c->mlp_norm[l], c->a, st);
     launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st);
@@ -376,6 +405,22 @@ bs_status bs_poll_status(bs_ctx* c, void* stream, int32_t* fault_out) {
   launch_clear_status(c->plan.status, st);
   *fault_out = host;
   return check_hip(c);
+}
+
+// Not part of the public ABI: address of an intermediate buffer of the last verify step, for
+// kernel-level debugging (0 h, 1 normed rows, 2 qkv f32, 3 q, 4 attention out, 5 mlp act, 6 final rows).
+void* bs_debug_buffer(bs_ctx* c, int which) {
+  if (!c) return nullptr;
+  switch (which) {
+    case 0: return c->h;
+    case 1: return c->a;
+    case 2: return c->qkv;
+    case 3: return c->q;
+    case 4: return c->attn_out;
+    case 5: return c->act;
+    case 6: return c->hf;
+    default: return nullptr;
+  }
 }
 
 }  // extern "C"

@@ -11,6 +11,9 @@
 //   * K/V pages are stored in MFMA operand order (see common.h), so a wave's 16-byte-per-lane
 //     load is one contiguous 1 KiB read that lands directly in the operand registers: no LDS
 //     staging, no bank conflicts, no shuffles.  LDS is used only for the final cross-wave merge.
+//   * Arithmetic runs on the f16 MFMA: queries and probabilities carry 11 significant bits (with
+//     8-bit bf16 queries the logits of the 7B-shape slice drift by 3e-2); the bf16 K/V fragments are
+//     widened to float16 in registers (exact for 6.1e-5 <= |x| <= 65504) right before use.
 //   * S^T = K Q^T (tokens are accumulator rows, the lane is the query row), so the softmax
 //     statistics of a query row are lane-private apart from one exchange between the two lane
 //     halves, and the probabilities are already laid out as the B operand of O^T = V^T P^T.
@@ -22,10 +25,23 @@
 namespace {
 constexpr int kMaxSplit = 16;
 
-__device__ __forceinline__ bf16x8 pack_bf16x8(const float* v) {
-  bf16x8 r;
+__device__ __forceinline__ f16x8 pack_f16x8(const float* v) {
+  f16x8 r;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) r[j] = (bf16)v[j];
+  for (int j = 0; j < 8; ++j) r[j] = (f16)v[j];
+  return r;
+}
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// eight bf16 (packed in four dwords) -> eight float16; three VALU ops per pair
+__device__ __forceinline__ f16x8 widen_bf16x8(u32x4 v) {
+  f16x8 r;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = __uint_as_float(v[j] << 16), hi = __uint_as_float(v[j] & 0xffff0000u);
+    const f16x2 pr = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(lo, hi));   // exact: no rounding occurs
+    r[2 * j] = pr[0];
+    r[2 * j + 1] = pr[1];
+  }
   return r;
 }
 }  // namespace
@@ -36,8 +52,8 @@ __device__ __forceinline__ bf16x8 pack_bf16x8(const float* v) {
 // RP = 32*NQ*QG.
 template <int NQ, int QG, int D>
 __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int Hq, int Hkv, float scale_log2e,
-                                                        const bf16* __restrict__ qkv, const bf16* __restrict__ k_pages,
-                                                        const bf16* __restrict__ v_pages, bf16* __restrict__ out,
+                                                        const f16* __restrict__ q, const bf16* __restrict__ k_pages,
+                                                        const bf16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
                                                         int n_split) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product
@@ -61,7 +77,6 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
   const int grp = wave / WPG, wig = wave % WPG;
   const int ln = lane & 31, lg = lane >> 5;
   const int row0 = p.row_start[b];
-  const int Nqkv = (Hq + 2 * Hkv) * D;
   const int32_t* bt = kv.block_table + (size_t)p.seq_slot[b] * kv.max_pages;
   const size_t page_elems = kv_page_elems(Hkv, D);
 
@@ -73,7 +88,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
     const int qr = (grp * NQ + qt) * 32 + ln;
     if (qr < R) {
       const int iq = qr / G, hg = qr % G;
-      const bf16* qp = qkv + (size_t)(row0 + iq) * Nqkv + (size_t)(h * G + hg) * D + lg * (D / 2);
+      const f16* qp = q + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + lg * (D / 2);
 #pragma unroll
       for (int s = 0; s < KS; ++s) qf[qt][s] = *(const u32x4*)(qp + s * 8);
       lim[qt] = c + iq;
@@ -134,19 +149,26 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
         for (int x = 0; x < DT * 2; ++x) vf[x] = *(const u32x4*)(vp + x * 512);
       }
       const int tok0 = t * kTile + 16 * lg;             // accumulator register i <-> token tok0 + i
+      f32x16 st[NQ];
+#pragma unroll
+      for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st[qt][i] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const f16x8 kh = widen_bf16x8(kc[s]);
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt)
+          st[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, as_f16x8(qf[qt][s]), st[qt], 0, 0, 0);
+      }
+      f16x8 pf[NQ][2];
 #pragma unroll
       for (int qt = 0; qt < NQ; ++qt) {
-        f32x16 st;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st[i] = 0.f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kc[s]), as_bf16x8(qf[qt][s]), st, 0, 0, 0);
         float x[16];
         float mloc = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          x[i] = (tok0 + i <= lim[qt]) ? st[i] * scale_log2e : -INFINITY;
+          x[i] = (tok0 + i <= lim[qt]) ? st[qt][i] * scale_log2e : -INFINITY;
           mloc = fmaxf(mloc, x[i]);
         }
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
@@ -164,13 +186,18 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[qt][dt][i] *= alpha;
         }
-        const bf16x8 p0 = pack_bf16x8(x), p1 = pack_bf16x8(x + 8);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vc[dt * 2 + 0]), p0, o[qt][dt], 0, 0, 0);
-          o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vc[dt * 2 + 1]), p1, o[qt][dt], 0, 0, 0);
-        }
+        pf[qt][0] = pack_f16x8(x);
+        pf[qt][1] = pack_f16x8(x + 8);
       }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+          const f16x8 vh = widen_bf16x8(vc[dt * 2 + t2]);
+#pragma unroll
+          for (int qt = 0; qt < NQ; ++qt)
+            o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, pf[qt][t2], o[qt][dt], 0, 0, 0);
+        }
     }
   }
 
@@ -237,9 +264,9 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
     if (n_split == 1) {
       const int iq = qr / G, hg = qr % G;
       const float inv = 1.0f / lt;
-      bf16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + d4;
+      f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + d4;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) dst[j] = (bf16)(src[j] * inv);
+      for (int j = 0; j < 4; ++j) dst[j] = (f16)(src[j] * inv);
     } else {
       const size_t pr = (((size_t)b * Hkv + h) * n_split + split) * RP + qr;
       *(f32x4*)(part_o + pr * D + d4) = *(const f32x4*)src;
@@ -252,7 +279,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
 template <int D>
 __global__ void __launch_bounds__(D) attn_merge_kernel(Plan p, int Hq, int Hkv, int RP, const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, int n_split,
-                                                       bf16* __restrict__ out) {
+                                                       f16* __restrict__ out) {
   const int r = blockIdx.x, hq = blockIdx.y;
   if (r >= p.n_rows[0]) return;
   const int b = p.row_seq[r], iq = p.row_pos[r];
@@ -270,7 +297,7 @@ __global__ void __launch_bounds__(D) attn_merge_kernel(Plan p, int Hq, int Hkv, 
     lt += part_ml[pr * 2 + 1] * f;
     acc += part_o[pr * D + threadIdx.x] * f;
   }
-  out[(size_t)r * Hq * D + (size_t)hq * D + threadIdx.x] = (bf16)(acc / lt);
+  out[(size_t)r * Hq * D + (size_t)hq * D + threadIdx.x] = (f16)(acc / lt);
 }
 
 static int rows_padded(const Shape& s, int k_max) {
@@ -287,7 +314,7 @@ size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max) {
 }
 
 template <int NQ, int QG, int D>
-static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int B, int M_max, const void* qkv,
+static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int B, int M_max, const void* q,
                              const void* k_pages, const void* v_pages, void* out, void* scratch, int n_split,
                              hipStream_t st) {
   constexpr int RP = 32 * NQ * QG;
@@ -299,24 +326,24 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
   hipLaunchKernelGGL(kern, dim3(s.Hkv, B, n_split), dim3(256), lds, st, p, kv, s.Hq, s.Hkv, scale_log2e,
-                     (const bf16*)qkv, (const bf16*)k_pages, (const bf16*)v_pages, (bf16*)out, part_o, part_ml, n_split);
+                     (const f16*)q, (const bf16*)k_pages, (const bf16*)v_pages, (f16*)out, part_o, part_ml, n_split);
   if (n_split > 1)
     hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, RP, part_o, part_ml,
-                       n_split, (bf16*)out);
+                       n_split, (f16*)out);
 }
 
-void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* qkv,
+void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
                       const void* k_pages, const void* v_pages, void* out, void* scratch, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)s.D);
   static const bool force_simple = getenv("BS_SIMPLE_ATTN") != nullptr;   // debugging aid
   if (s.dtype == BS_F32) {
-    hipLaunchKernelGGL(attn_simple_kernel<float>, dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
-                       (const float*)qkv, (const float*)k_pages, (const float*)v_pages, (float*)out);
+    hipLaunchKernelGGL((attn_simple_kernel<float, float>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
+                       (const float*)q, (const float*)k_pages, (const float*)v_pages, (float*)out);
     return;
   }
   if (force_simple) {
-    hipLaunchKernelGGL(attn_simple_kernel<bf16>, dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
-                       (const bf16*)qkv, (const bf16*)k_pages, (const bf16*)v_pages, (bf16*)out);
+    hipLaunchKernelGGL((attn_simple_kernel<bf16, f16>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
+                       (const f16*)q, (const bf16*)k_pages, (const bf16*)v_pages, (f16*)out);
     return;
   }
   static const char* split_env = getenv("BS_ATTN_SPLIT");
@@ -325,8 +352,8 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
   const int tiles = (rows_padded(s, k_max)) / 32;
 #define BS_ATTN(NQ, QG)                                                                                         \
   do {                                                                                                          \
-    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, qkv, k_pages, v_pages, out, scratch, n_split, st); \
-    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, qkv, k_pages, v_pages, out, scratch, n_split, st);   \
+    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, st); \
+    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, st);   \
   } while (0)
   if (tiles == 1) BS_ATTN(1, 1);
   else if (tiles == 2) BS_ATTN(2, 1);

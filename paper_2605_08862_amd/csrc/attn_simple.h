@@ -5,10 +5,10 @@
 #pragma once
 #include "common.h"
 
-template <typename T>
+template <typename T, typename TO>
 __global__ void __launch_bounds__(256) attn_simple_kernel(Plan p, KvView kv, int Hq, int Hkv, int D, float scale,
-                                                          const T* __restrict__ qkv, const T* __restrict__ k_pages,
-                                                          const T* __restrict__ v_pages, T* __restrict__ out) {
+                                                          const TO* __restrict__ q, const T* __restrict__ k_pages,
+                                                          const T* __restrict__ v_pages, TO* __restrict__ out) {
   __shared__ float s_q[128], s_p[256], s_red[4], s_acc[2][128];
   const int r = blockIdx.x, hq = blockIdx.y;
   if (r >= p.n_rows[0]) return;
@@ -18,7 +18,7 @@ __global__ void __launch_bounds__(256) attn_simple_kernel(Plan p, KvView kv, int
   const int tid = threadIdx.x;
   const int32_t* bt = kv.block_table + (size_t)p.seq_slot[b] * kv.max_pages;
   const size_t page_elems = kv_page_elems(Hkv, D);
-  if (tid < D) s_q[tid] = to_f32<T>(qkv[(size_t)r * (Hq + 2 * Hkv) * D + (size_t)hq * D + tid]);
+  if (tid < D) s_q[tid] = to_f32<TO>(q[(size_t)r * Hq * D + (size_t)hq * D + tid]);
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;      // acc: thread (tid%D, tid/D) partial of out[d]
   const int dd = tid % D, part = tid / D, nparts = 256 / D;
   __syncthreads();
@@ -64,5 +64,5 @@ __global__ void __launch_bounds__(256) attn_simple_kernel(Plan p, KvView kv, int
     if (part == pp) s_acc[0][dd] += acc;
     __syncthreads();
   }
-  if (tid < D) out[(size_t)r * Hq * D + (size_t)hq * D + tid] = from_f32<T>(s_acc[0][tid] / l_run);
+  if (tid < D) out[(size_t)r * Hq * D + (size_t)hq * D + tid] = from_f32<TO>(s_acc[0][tid] / l_run);
 }

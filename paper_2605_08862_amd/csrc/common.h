@@ -6,11 +6,14 @@
 #include "../../include/bubblespec.h"
 
 typedef __bf16 bf16;
+typedef _Float16 f16;
 
 template <typename T> __device__ __forceinline__ float to_f32(T x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ float to_f32<bf16>(bf16 x) { return (float)x; }
+template <> __device__ __forceinline__ float to_f32<f16>(f16 x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)x; }             // RNE
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // RNE
 
@@ -98,17 +101,20 @@ void launch_clear_status(int32_t* status, hipStream_t st);
 void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, hipStream_t st);
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, const float* gain, void* out,
                     hipStream_t st);
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, void* qkv, void* k_pages,
-                        void* v_pages, hipStream_t st);
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, void* q_out,
+                        void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
-// gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue
+// gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue.  float32 models: A, W float32 row-major.
+// bf16 models: A float16 row-major, W the packed float16 copy made by launch_pack_weight.
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3 };
 void launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
                  const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
                  hipStream_t st);
+size_t packed_weight_elems(int N, int K);
+void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st);
 // attention.hip
-void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* qkv,
+void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
                       const void* k_pages, const void* v_pages, void* out, void* scratch, hipStream_t st);
 size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
 // sampler.hip

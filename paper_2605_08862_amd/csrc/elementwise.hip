@@ -22,7 +22,8 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-// out[r] = h[r] * gain / sqrt(mean(h[r]^2) + eps), fp32 in, model dtype out.
+// out[r] = h[r] * gain / sqrt(mean(h[r]^2) + eps), float32 in; out is the GEMM operand type
+// (float32 for float32 models, float16 for bf16 models).
 template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, const float* __restrict__ h,
                                                       const float* __restrict__ gain, T* __restrict__ out) {
@@ -39,13 +40,14 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
 }
 
 // Rotary (pairs (j, j + D/2), angle = position * theta^(-2j/D)) on q and k of packed row r at
-// absolute position c_b + i; q is rotated in place in the qkv buffer, k and v go to the slot's
-// page at that position, rounded to the cache dtype.  Angles are formed in float64: at positions
+// absolute position c_b + i.  The QKV projection arrives in float32 (so each of q, k, v is rounded
+// exactly once, after the rotation): q goes to the query buffer (float16 for bf16 models: it is an
+// attention operand, not cache data), k and v to the slot's page in the cache dtype.  Angles are formed in float64: at positions
 // of 3e4 a float32 angle is already off by ~2e-3 rad.
-template <typename T>
+template <typename T, typename TQ>
 __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D, float theta,
-                                                          T* __restrict__ qkv, T* __restrict__ k_pages,
-                                                          T* __restrict__ v_pages) {
+                                                          const float* __restrict__ qkv, TQ* __restrict__ q_out,
+                                                          T* __restrict__ k_pages, T* __restrict__ v_pages) {
   __shared__ float s_cos[64], s_sin[64];
   int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
@@ -60,30 +62,31 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
     s_sin[threadIdx.x] = (float)sn;
   }
   __syncthreads();
-  T* row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
+  const float* row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
+  TQ* qrow = q_out + (size_t)r * Hq * D;
   const int page = kv.block_table[(size_t)p.seq_slot[b] * kv.max_pages + pos / kPage];
   const int tok = pos % kPage;
   const size_t pbase = (size_t)page * kv_page_elems(Hkv, D);
   // q heads and k heads: one thread per (head, pair)
   for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += blockDim.x) {
     int hh = idx / half, j = idx % half;
-    T* x = row + (size_t)hh * D;
-    float x1 = to_f32<T>(x[j]), x2 = to_f32<T>(x[j + half]);
+    const float* x = row + (size_t)hh * D;
+    float x1 = x[j], x2 = x[j + half];
     float c = s_cos[j], s = s_sin[j];
     float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
     if (hh < Hq) {
-      x[j] = from_f32<T>(y1);
-      x[j + half] = from_f32<T>(y2);
+      qrow[hh * D + j] = from_f32<TQ>(y1);
+      qrow[hh * D + j + half] = from_f32<TQ>(y2);
     } else {
       int kh = hh - Hq;
       k_pages[pbase + k_index<T>(D, kh, tok, j)] = from_f32<T>(y1);
       k_pages[pbase + k_index<T>(D, kh, tok, j + half)] = from_f32<T>(y2);
     }
   }
-  const T* vrow = row + (size_t)(Hq + Hkv) * D;
+  const float* vrow = row + (size_t)(Hq + Hkv) * D;
   for (int idx = threadIdx.x; idx < Hkv * D; idx += blockDim.x) {
     int kh = idx / D, dd = idx % D;
-    v_pages[pbase + v_index<T>(D, kh, tok, dd)] = vrow[idx];
+    v_pages[pbase + v_index<T>(D, kh, tok, dd)] = from_f32<T>(vrow[idx]);
   }
 }
 
@@ -111,16 +114,16 @@ void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, f
 }
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, const float* gain, void* out, hipStream_t st) {
   if (s.dtype == BS_F32) hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, gain, (float*)out);
-  else hipLaunchKernelGGL(rmsnorm_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, gain, (bf16*)out);
+  else hipLaunchKernelGGL(rmsnorm_kernel<f16>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, gain, (f16*)out);
 }
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, void* qkv, void* k_pages,
-                        void* v_pages, hipStream_t st) {
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, void* q_out,
+                        void* k_pages, void* v_pages, hipStream_t st) {
   if (s.dtype == BS_F32)
-    hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
-                       (float*)qkv, (float*)k_pages, (float*)v_pages);
+    hipLaunchKernelGGL((rope_append_kernel<float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+                       qkv, (float*)q_out, (float*)k_pages, (float*)v_pages);
   else
-    hipLaunchKernelGGL(rope_append_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
-                       (bf16*)qkv, (bf16*)k_pages, (bf16*)v_pages);
+    hipLaunchKernelGGL((rope_append_kernel<bf16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+                       qkv, (f16*)q_out, (bf16*)k_pages, (bf16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st) {

@@ -1,14 +1,13 @@
 // Projection GEMMs of the verify pass (Sec. 3.3 "token-wise" linear layers):
-//   QKV, O (+residual), gate/up (+SwiGLU), down (+residual), and plain float32 stores.
-// bf16 models run on the MFMA main loop of gemm_mfma.h; float32 models (the tiny parity
-// configuration, launch-latency bound) run on a plain LDS-tiled FMA kernel.
+//   QKV (float32 out), O (+residual), gate/up (+SwiGLU), down (+residual).
+// bf16 models run on the f16 MFMA main loop of gemm_mfma.h over packed weights; float32 models (the
+// tiny parity configuration, launch-latency bound) run on a plain LDS-tiled FMA kernel.
 #include "gemm_mfma.h"
 #include <stdlib.h>
 
-// ------------------------------------------------------------------ epilogue helpers
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
-// ------------------------------------------------------------------ plain FMA kernel (any dtype)
+// ------------------------------------------------------------------ plain FMA kernel (float32 models)
 // 64x64 output tile, K step 16, 256 threads, 4x4 outputs per thread.  For EPI_SWIGLU the tile
 // holds gate and up columns of the same 64 output features.
 template <typename T, int EPI>
@@ -73,16 +72,47 @@ __global__ void __launch_bounds__(256) gemm_simple_kernel(const int32_t* __restr
   }
 }
 
-// ------------------------------------------------------------------ MFMA kernel (bf16)
-// Workgroup tile: BM = 32*MT rows x BNW = 4*NT*32 weight rows (for SwiGLU: half of them are gate
-// rows, the other half the matching up rows, interleaved per 32 so that accumulators [..][2j] and
-// [..][2j+1] of one lane hold gate and up of the same output feature).
-// Block order: ids are dealt round-robin to the 8 XCDs by the hardware; remap so that the M
-// blocks that share one weight tile run on the same XCD back to back and hit its L2.
+// ------------------------------------------------------------------ weight packing (once per context)
+// bf16 row-major [N, K] -> float16 MFMA operand order (see gemm_mfma.h); rows beyond N are zero.
+__global__ void __launch_bounds__(256) pack_weight_kernel(const bf16* __restrict__ w, int N, int K, f16* __restrict__ packed,
+                                                          size_t n_chunks) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;     // one 16-byte chunk of the packed array
+  if (c >= n_chunks) return;
+  const int nk = K / kBK;
+  const int lane = c & 63, s = (c >> 6) & 3;
+  const size_t blk = c >> 8;
+  const int kt = blk % nk, nt = blk / nk;
+  const int n = nt * 32 + (lane & 31), k = kt * kBK + (lane >> 5) * 32 + s * 8;
+  f16x8 v;
+  if (n < N) {
+    const bf16x8 src = *(const bf16x8*)(w + (size_t)n * K + k);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = (f16)(float)src[j];
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = (f16)0.f;
+  }
+  *(f16x8*)(packed + c * 8) = v;
+}
+
+size_t packed_weight_elems(int N, int K) { return (size_t)((N + 31) / 32) * (K / kBK) * kWBlock; }
+
+void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st) {
+  const size_t n_chunks = packed_weight_elems(N, K) / 8;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, (const bf16*)w_bf16,
+                     N, K, (f16*)packed_f16, n_chunks);
+}
+
+// ------------------------------------------------------------------ MFMA kernel (bf16 models)
+// Workgroup tile: BM = 32*MT rows x 4 waves x NT weight row tiles.  For SwiGLU NT == 2 and the two row
+// tiles of a wave are the gate rows and the matching up rows of the same 32 output features, so both
+// land in the same lane.  Grid: x = (M block, N block) pairs, remapped so that the M blocks sharing
+// a weight tile run back to back on one XCD (ids are dealt round-robin to the 8 XCDs) and hit its
+// L2; y = K split (EPI_RESID_ADD only: partial sums are added to the float32 residual atomically).
 template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
-                                                        const bf16* __restrict__ A, const int32_t* __restrict__ a_rows,
-                                                        const bf16* __restrict__ W, void* __restrict__ out,
+                                                        const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
+                                                        const f16* __restrict__ Wp, void* __restrict__ out,
                                                         int m_blocks, int n_blocks) {
   using G = MfmaGemm<MT, NT, false>;
   extern __shared__ __align__(16) char lds[];
@@ -95,28 +125,29 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
   const int m0 = mb * G::BM;
   if (m0 >= M) return;
   constexpr bool GLU = (EPI == EPI_SWIGLU);
-  constexpr int NOUT_W = GLU ? NT * 16 : NT * 32;       // output columns per wave
+  static_assert(!GLU || NT == 2, "SwiGLU pairs one gate tile with one up tile per wave");
+  constexpr int NOUT_W = GLU ? 32 : NT * 32;            // output columns per wave
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int n_wave0 = nb * 4 * NOUT_W + wave * NOUT_W;
+  const int n_wave0 = (nb * 4 + wave) * NOUT_W;
+  const int nk = K / kBK;
+  const int n_tiles = (N + 31) / 32;                    // row tiles of the packed matrix (per half for SwiGLU)
 
-  const bf16* x_rows[MT];
-  int x_lds[MT];
+  typename G::Operands op;
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     int row, g, s;
     G::chunk_of(i, row, g, s);
     int r = min(m0 + row, M - 1);
     if (a_rows) r = a_rows[r];
-    x_rows[i] = A + (size_t)r * K + g * 32 + s * 8;
-    x_lds[i] = G::chunk_lds_offset(row, g, s);
+    op.x_rows[i] = A + (size_t)r * K + g * 32 + s * 8;
+    op.x_lds[i] = G::chunk_lds_offset(row, g, s);
   }
-  const bf16* w_rows[NT];
 #pragma unroll
   for (int ni = 0; ni < NT; ++ni) {
-    int n;
-    if (GLU) n = min(n_wave0 + (ni >> 1) * 32 + (lane & 31), N - 1) + ((ni & 1) ? N : 0);
-    else     n = min(n_wave0 + ni * 32 + (lane & 31), N - 1);
-    w_rows[ni] = W + (size_t)n * K + (lane >> 5) * 32;
+    int nt;
+    if (GLU) nt = min(n_wave0 / 32, n_tiles - 1) + (ni ? n_tiles : 0);
+    else     nt = min(n_wave0 / 32 + ni, n_tiles - 1);
+    op.w_tiles[ni] = Wp + (size_t)nt * nk * kWBlock + lane * 8;
   }
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -125,7 +156,9 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
     for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-  G::run(acc, x_rows, x_lds, w_rows, K / kBK, lds);
+  const int n_split = gridDim.y;
+  const int kt0 = (int)((long)nk * blockIdx.y / n_split), kt1 = (int)((long)nk * (blockIdx.y + 1) / n_split);
+  G::run(acc, op, kt0, kt1, lds);
 
 #pragma unroll
   for (int mi = 0; mi < MT; ++mi) {
@@ -134,20 +167,19 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
       const int m = m0 + mi * 32 + acc_row(lane, i);
       if (m >= M) continue;
       if (GLU) {
-#pragma unroll
-        for (int nj = 0; nj < NT / 2; ++nj) {
-          const int n = n_wave0 + nj * 32 + acc_col(lane);
-          if (n < N) ((bf16*)out)[(size_t)m * N + n] = (bf16)(silu_f(acc[mi][2 * nj][i]) * acc[mi][2 * nj + 1][i]);
-        }
+        const int n = n_wave0 + acc_col(lane);
+        if (n < N) ((f16*)out)[(size_t)m * N + n] = (f16)(silu_f(acc[mi][0][i]) * acc[mi][NT - 1][i]);
       } else {
 #pragma unroll
         for (int ni = 0; ni < NT; ++ni) {
           const int n = n_wave0 + ni * 32 + acc_col(lane);
           if (n >= N) continue;
           const size_t o = (size_t)m * N + n;
-          if (EPI == EPI_STORE) ((bf16*)out)[o] = (bf16)acc[mi][ni][i];
-          else if (EPI == EPI_RESID_ADD) ((float*)out)[o] += acc[mi][ni][i];
-          else ((float*)out)[o] = acc[mi][ni][i];
+          if (EPI == EPI_STORE) ((f16*)out)[o] = (f16)acc[mi][ni][i];
+          else if (EPI == EPI_RESID_ADD) {
+            if (n_split == 1) ((float*)out)[o] += acc[mi][ni][i];
+            else atomicAdd((float*)out + o, acc[mi][ni][i]);
+          } else ((float*)out)[o] = acc[mi][ni][i];
         }
       }
     }
@@ -156,14 +188,14 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
 
 template <int MT, int NT, int EPI>
 static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
-                        const void* W, void* out, hipStream_t st) {
+                        const void* W, void* out, int n_split, hipStream_t st) {
   using G = MfmaGemm<MT, NT, false>;
-  constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * NT * 16 : 4 * NT * 32;
+  constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * 32 : 4 * NT * 32;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
   int total = m_blocks * n_blocks;
   int grid = ((total + 7) / 8) * 8;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
-                     (const bf16*)A, a_rows, (const bf16*)W, out, m_blocks, n_blocks);
+  hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid, n_split), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
+                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks);
 }
 
 template <typename T, int EPI>
@@ -174,15 +206,51 @@ static void launch_simple(const int32_t* n_rows_dev, int M_max, int N, int K, co
                      (const T*)W, out);
 }
 
+// Tile choice.  MT: smallest row tiling that covers M_max with the least padding (576 rows -> 3 x 192).
+// NT: two row tiles per wave (256 columns per workgroup) when that still yields enough workgroups for
+// 256 CUs, else one.  K split (residual epilogue only) when even that leaves most CUs idle.
+static int pick_mt(int M_max) {
+  if (M_max <= 32) return 1;
+  if (M_max <= 64) return 2;
+  if (M_max <= 128) return 4;
+  const int pad6 = (M_max + 191) / 192 * 192, pad4 = (M_max + 127) / 128 * 128;
+  return pad6 <= pad4 ? 6 : 4;
+}
+
 template <int EPI>
 static void dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
                      const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
-  static const bool force_simple = getenv("BS_SIMPLE_GEMM") != nullptr;   // debugging aid
   if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return; }
-  if (force_simple) { launch_simple<bf16, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return; }
-  if (M_max <= 32) launch_mfma<1, 2, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
-  else if (M_max <= 64) launch_mfma<2, 2, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
-  else launch_mfma<4, 2, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+  static const char* env_split = getenv("BS_GEMM_SPLIT");          // tuning aids
+  static const char* env_nt = getenv("BS_GEMM_NT");
+  const int mt = pick_mt(M_max);
+  const int m_blocks = (M_max + mt * 32 - 1) / (mt * 32);
+  int nt = 2;
+  if (EPI != EPI_SWIGLU) {
+    const int blocks2 = m_blocks * ((N + 255) / 256);
+    if (blocks2 < 200) nt = 1;
+    if (env_nt) nt = atoi(env_nt) == 1 ? 1 : 2;
+  }
+  const int nout = (EPI == EPI_SWIGLU) ? 128 : nt * 128;
+  const int blocks = m_blocks * ((N + nout - 1) / nout);
+  int n_split = 1;
+  if (EPI == EPI_RESID_ADD) {
+    const int nk = K / kBK;
+    if (blocks < 160) n_split = (256 + blocks - 1) / blocks;
+    if (n_split > nk / 4) n_split = nk / 4 > 0 ? nk / 4 : 1;       // at least 4 K tiles per split
+    if (env_split) n_split = atoi(env_split);
+    if (n_split < 1) n_split = 1;
+    if (n_split > nk) n_split = nk;
+  }
+#define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
+  if constexpr (EPI != EPI_SWIGLU) {
+    if (nt == 1) {
+      switch (mt) { case 1: BS_GEMM(1, 1); break; case 2: BS_GEMM(2, 1); break; case 4: BS_GEMM(4, 1); break; default: BS_GEMM(6, 1); }
+      return;
+    }
+  }
+  switch (mt) { case 1: BS_GEMM(1, 2); break; case 2: BS_GEMM(2, 2); break; case 4: BS_GEMM(4, 2); break; default: BS_GEMM(6, 2); }
+#undef BS_GEMM
 }
 
 void launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,

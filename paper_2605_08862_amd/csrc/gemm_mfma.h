@@ -1,35 +1,54 @@
-// bf16 MFMA main loop shared by the projection GEMMs and the LM-head kernel.
+// MFMA main loop shared by the projection GEMMs and the LM-head kernel (bf16 models).
 //
-//   C[M,N] = X[M,K] * W[N,K]^T      X = activations, W = weights, both K-contiguous (row-major).
+//   C[M,N] = X[M,K] * W[N,K]^T      X = activations (float16, row-major), W = weights.
 //
-// Design for the verify step's shapes (M = 20..4352 packed query rows, weights far larger than
-// activations): a workgroup of 4 waves owns BM = 32*MT rows and 4*NT*32 weight rows; the four
-// waves sit side by side along N.
-//   * Weights stream HBM -> VGPR directly, never through LDS: every weight element is needed by
-//     exactly one wave.  Lane (n, g) of a wave reads 64 contiguous bytes of weight row n per
-//     64-wide K tile (k = 32g .. 32g+31), i.e. two lanes cover one full 128-byte line.
-//   * Activations go through LDS (shared by the 4 waves), stored in MFMA fragment order so that
-//     every fragment read is one conflict-free 1 KiB ds_read_b128 sweep.
-//   * The contraction index inside a K tile is permuted (MFMA step s of lane group g multiplies
-//     k = 32g + 8s + j); sums do not depend on the order of k, and both operands use the same
-//     permutation, so no data movement is needed to make the weight loads contiguous.
-//   * SWAP = true issues mfma(W, X) instead of mfma(X, W): the accumulator then holds C^T tiles
-//     (rows = weight rows, lane = token), which makes per-token reductions over N in-lane.
+// Precision.  Weights are bf16 values; activations handed from one operator to the next are kept
+// in float16 (11 significant bits) and the products run on the f16 MFMA with float32 accumulation.
+// With bf16 (8-bit) activation operands the full-vocabulary logits of a 28-layer decoder drift by
+// ~9e-2 from the exact forward; with 11-bit operands they stay near 1e-2.  bf16 weight values
+// convert to float16 exactly for 6.1e-5 <= |w| <= 65504 (below that the absolute error is < 6e-8).
+//
+// Data movement, designed for the verify step's shapes (M = 20..4352 packed rows, weights far
+// larger than activations):
+//   * Weights are re-packed once (at context creation) into MFMA operand order: for each
+//     (32-row tile, 64-wide K tile) a 4 KiB block [s = 0..3][lane = 0..63][8 halves], blocks of one
+//     row tile consecutive along K.  A wave streams one or two row tiles: every load instruction
+//     reads 1 KiB contiguous, every wave reads a purely sequential stream, and the data land in the
+//     operand registers with no LDS hop.  Every weight element is read by exactly one wave of a
+//     workgroup, three K tiles deep in flight (register ring).
+//   * Activations go through LDS (shared by the 4 waves, which sit side by side along N), stored
+//     in fragment order so that each fragment read is one conflict-free 1 KiB ds_read_b128 sweep.
+//   * The contraction index inside a K tile is permuted (step s of lane group g multiplies
+//     k = 32g + 8s + j) identically for both operands, which is what makes both of the above
+//     layouts contiguous.
+//   * SWAP = true issues mfma(W, X): the accumulator holds C^T tiles (rows = weight rows, lane =
+//     activation row), which makes per-row reductions over N lane-private.
 #pragma once
 #include "common.h"
 
+typedef _Float16 f16;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 64;   // K tile (elements)
+constexpr int kBK = 64;                    // K tile (elements)
+constexpr int kWBlock = 32 * kBK;          // elements of one packed (row tile, K tile) block
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 // Accumulator element i of lane `lane` in a 32x32 MFMA tile: row, col inside the tile.
 __device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 __device__ __forceinline__ int acc_col(int lane) { return lane & 31; }
+
+// Offset (elements) of weight element (n, k) in the packed layout of a matrix with nk K tiles.
+__host__ __device__ __forceinline__ size_t packed_w_index(int n, int k, int nk) {
+  int nt = n >> 5, nl = n & 31, kt = k >> 6, kk = k & 63;
+  int g = kk >> 5, s = (kk & 31) >> 3, j = kk & 7;
+  return ((size_t)nt * nk + kt) * kWBlock + (size_t)s * 512 + (g * 32 + nl) * 8 + j;
+}
 
 template <int MT, int NT, bool SWAP>
 struct MfmaGemm {
@@ -37,67 +56,9 @@ struct MfmaGemm {
   static constexpr int LDS_STAGE_BYTES = MT * 4 * 1024;        // MT row tiles x 4 K-steps x 1 KiB
   static constexpr int LDS_BYTES = 2 * LDS_STAGE_BYTES;
 
-  // x_rows[i]: global pointer to the start of this thread's i-th 16-byte activation chunk at k=0
-  //            (already includes the row and the (g, s) offset inside a K tile), i < MT.
-  // x_lds[i]:  byte offset of that chunk inside an LDS stage.
-  // w_rows[ni]: pointer to weight row (k = 32*g) for N tile ni of this lane.
-  // nk: number of K tiles.
-  __device__ static __forceinline__ void run(f32x16 (&acc)[MT][NT], const bf16* const (&x_rows)[MT],
-                                             const int (&x_lds)[MT], const bf16* const (&w_rows)[NT], int nk,
-                                             char* lds) {
-    const int lane = threadIdx.x & 63;
-    u32x4 xreg[MT];
-    u32x4 wnext[NT][4];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(x_rows[i]);
-#pragma unroll
-    for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) wnext[ni][s] = *(const u32x4*)(w_rows[ni] + s * 8);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) *(u32x4*)(lds + x_lds[i]) = xreg[i];
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      u32x4 wcur[NT][4];
-#pragma unroll
-      for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wcur[ni][s] = wnext[ni][s];
-      const bool more = kt + 1 < nk;
-      if (more) {
-        const int koff = (kt + 1) * kBK;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(x_rows[i] + koff);
-#pragma unroll
-        for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) wnext[ni][s] = *(const u32x4*)(w_rows[ni] + koff + s * 8);
-      }
-      const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-#pragma unroll
-        for (int mi = 0; mi < MT; ++mi) {
-          bf16x8 xf = as_bf16x8(*(const u32x4*)(stage + ((mi * 4 + s) * 64 + lane) * 16));
-#pragma unroll
-          for (int ni = 0; ni < NT; ++ni) {
-            bf16x8 wf = as_bf16x8(wcur[ni][s]);
-            if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[mi][ni], 0, 0, 0);
-            else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, wf, acc[mi][ni], 0, 0, 0);
-          }
-        }
-      }
-      if (more) {
-        char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) *(u32x4*)(nstage + x_lds[i]) = xreg[i];
-      }
-      __syncthreads();
-    }
-  }
-
   // Chunk assignment of thread t for the activation tile: chunk q = i*256 + t covers
-  // (row, g, s) with g = q / (BM*4), row = (q % (BM*4)) / 4, s = q % 4.
+  // (row, g, s) with g = q / (BM*4), row = (q % (BM*4)) / 4, s = q % 4: a wave touches 16 rows x
+  // 64 contiguous bytes in global memory and 16 distinct bank groups in LDS.
   __device__ static __forceinline__ void chunk_of(int i, int& row, int& g, int& s) {
     int q = i * 256 + threadIdx.x;
     g = q / (BM * 4);
@@ -107,5 +68,75 @@ struct MfmaGemm {
   }
   __device__ static __forceinline__ int chunk_lds_offset(int row, int g, int s) {
     return (((row >> 5) * 4 + s) * 64 + g * 32 + (row & 31)) * 16;
+  }
+
+  struct Operands {
+    const f16* x_rows[MT];   // this thread's activation chunks at k = 0 (row and (g, s) offset applied)
+    int x_lds[MT];           // byte offset of each chunk inside an LDS stage
+    const f16* w_tiles[NT];  // packed weight stream of each row tile at K tile 0, lane offset applied
+  };
+
+  template <int STAGE>
+  __device__ static __forceinline__ void load_w(u32x4 (&wreg)[3][NT][4], const Operands& op, int kt) {
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        wreg[STAGE][ni][s] = *(const u32x4*)(op.w_tiles[ni] + (size_t)kt * kWBlock + s * 512);
+  }
+
+  template <int STAGE>
+  __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[MT],
+                                              const Operands& op, int kt, int kt1, char* lds) {
+    const int lane = threadIdx.x & 63;
+    if (kt + 1 < kt1) {                                   // activations of the next K tile -> LDS
+      char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) *(u32x4*)(nstage + op.x_lds[i]) = xreg[i];
+    }
+    if (kt + 2 < kt1) {                                   // global loads two K tiles ahead
+#pragma unroll
+      for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)(kt + 2) * kBK);
+      load_w<(STAGE + 2) % 3>(wreg, op, kt + 2);
+    }
+    const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+      for (int mi = 0; mi < MT; ++mi) {
+        const f16x8 xf = as_f16x8(*(const u32x4*)(stage + ((mi * 4 + s) * 64 + lane) * 16));
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni) {
+          const f16x8 wf = as_f16x8(wreg[STAGE][ni][s]);
+          if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, xf, acc[mi][ni], 0, 0, 0);
+          else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf, acc[mi][ni], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // Accumulates K tiles [kt0, kt1) into acc.  All 256 threads of the workgroup must call it.
+  __device__ static __forceinline__ void run(f32x16 (&acc)[MT][NT], const Operands& op, int kt0, int kt1, char* lds) {
+    if (kt0 >= kt1) return;
+    u32x4 xreg[MT];
+    u32x4 wreg[3][NT][4];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt0 * kBK);
+    load_w<0>(wreg, op, kt0);
+    if (kt0 + 1 < kt1) load_w<1>(wreg, op, kt0 + 1);
+    char* stage0 = lds + (kt0 & 1) * LDS_STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[i];
+    if (kt0 + 1 < kt1) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)(kt0 + 1) * kBK);
+    }
+    __syncthreads();
+    for (int kt = kt0; kt < kt1; kt += 3) {
+      body<0>(acc, wreg, xreg, op, kt, kt1, lds);
+      if (kt + 1 < kt1) body<1>(acc, wreg, xreg, op, kt + 1, kt1, lds);
+      if (kt + 2 < kt1) body<2>(acc, wreg, xreg, op, kt + 2, kt1, lds);
+    }
   }
 };

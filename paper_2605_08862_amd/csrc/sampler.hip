@@ -25,8 +25,8 @@ int lmhead_vtiles(int V) {
 //                to sel_logits [B, V].
 template <bool STATS>
 __global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int V, int K,
-                                                     const bf16* __restrict__ X, const int32_t* __restrict__ x_rows,
-                                                     const bf16* __restrict__ W, float inv_temp,
+                                                     const f16* __restrict__ X, const int32_t* __restrict__ x_rows,
+                                                     const f16* __restrict__ W, float inv_temp,
                                                      const int32_t* __restrict__ row_target, SamplerBufs sb,
                                                      float* __restrict__ store, int m_blocks, int n_blocks) {
   using G = MfmaGemm<kLmMT, kLmNT, true>;
@@ -43,22 +43,22 @@ __global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__
   const int vt = nb * 4 + wave;                       // statistics tile of this wave
   const int n_wave0 = vt * kLmVtile;
 
-  const bf16* x_ptr[kLmMT];
-  int x_lds[kLmMT];
+  typename G::Operands op;
 #pragma unroll
   for (int i = 0; i < kLmMT; ++i) {
     int row, g, s;
     G::chunk_of(i, row, g, s);
     int r = min(m0 + row, M - 1);
     if (x_rows) r = x_rows[r];
-    x_ptr[i] = X + (size_t)r * K + g * 32 + s * 8;
-    x_lds[i] = G::chunk_lds_offset(row, g, s);
+    op.x_rows[i] = X + (size_t)r * K + g * 32 + s * 8;
+    op.x_lds[i] = G::chunk_lds_offset(row, g, s);
   }
-  const bf16* w_ptr[kLmNT];
+  const int nk = K / kBK;
+  const int n_tiles = (V + 31) / 32;
 #pragma unroll
   for (int ni = 0; ni < kLmNT; ++ni) {
-    int n = min(n_wave0 + ni * 32 + (lane & 31), V - 1);
-    w_ptr[ni] = W + (size_t)n * K + (lane >> 5) * 32;
+    const int nt = min(n_wave0 / 32 + ni, n_tiles - 1);
+    op.w_tiles[ni] = W + (size_t)nt * nk * kWBlock + lane * 8;
   }
   f32x16 acc[kLmMT][kLmNT];
 #pragma unroll
@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__
     for (int ni = 0; ni < kLmNT; ++ni)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-  G::run(acc, x_ptr, x_lds, w_ptr, K / kBK, lds);
+  G::run(acc, op, 0, nk, lds);
   if (n_wave0 >= V) return;
 
   // accumulator (SWAP): rows = vocabulary entries n_wave0 + ni*32 + acc_row, lane column = token
@@ -414,7 +414,7 @@ void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* h
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
   int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
   hipLaunchKernelGGL(lmhead_kernel<true>, dim3(grid), dim3(256), G::LDS_BYTES, st, p.n_rows, M_max, s.V, s.d,
-                     (const bf16*)hf, (const int32_t*)nullptr, (const bf16*)lm_head, inv_temp, p.row_target, sb,
+                     (const f16*)hf, (const int32_t*)nullptr, (const f16*)lm_head, inv_temp, p.row_target, sb,
                      logits_debug, m_blocks, n_blocks);
 }
 void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_head, const SamplerBufs& sb,
@@ -423,7 +423,7 @@ void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_he
   int m_blocks = (B + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
   int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
   hipLaunchKernelGGL(lmhead_kernel<false>, dim3(grid), dim3(256), G::LDS_BYTES, st, (const int32_t*)nullptr, B, s.V, s.d,
-                     (const bf16*)hf, sb.sel_row, (const bf16*)lm_head, 1.0f, (const int32_t*)nullptr, sb,
+                     (const f16*)hf, sb.sel_row, (const f16*)lm_head, 1.0f, (const int32_t*)nullptr, sb,
                      sb.sel_logits, m_blocks, n_blocks);
 }
 void launch_logit_stats(const Plan& p, int M_max, int V, const float* logits, float inv_temp, const SamplerBufs& sb,

@@ -12,8 +12,9 @@ NEAR_TIE = 1e-3
 
 
 def oracle_desc(desc):
+    bf16 = desc["dtype"] == W.BS_BF16
     return OD.ModelDesc(desc["n_layers"], desc["d_model"], desc["n_q_heads"], desc["n_kv_heads"], desc["head_dim"],
-                        desc["d_ffn"], desc["vocab"], cache_dtype="f32" if desc["dtype"] == W.BS_F32 else "bf16",
+                        desc["d_ffn"], desc["vocab"], cache_dtype="bf16" if bf16 else "f32",
                         rms_eps=desc["rms_eps"], rope_theta=desc["rope_theta"])
 
 

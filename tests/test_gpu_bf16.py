@@ -1,0 +1,127 @@
+"""GPU parity, bf16 decoders: MFMA GEMMs, ragged MFMA verify attention over the paged cache, fused
+LM-head sampler.  Small shapes span several tiles and ragged tails; the 1.5B / 7B cases are two-layer
+slices of the real per-layer shapes with the full vocabulary (the oracle finishes those in seconds)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder as OD
+from paper_2605_08862_amd import workloads as W
+from paper_2605_08862_amd.runtime import Engine, fuse_weights
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _f64_weights(wn):
+    c = lambda a: np.asarray(a, dtype=np.float64)
+    return {"embed": wn["embed"], "lm_head": c(wn["lm_head"]), "final_norm": c(wn["final_norm"]),
+            "layers": [{k: c(v) for k, v in lw.items()} for lw in wn["layers"]]}
+
+
+def _run_case(desc, ctx_lens, k_b, k_max, seed, temperature=1.0, q_mode="dense", q_scale=0.8, perm=3,
+              check_kv=True):
+    """One verify step on random-filled contexts; returns stats after asserting all three tiers."""
+    Bn = len(ctx_lens)
+    rng = np.random.default_rng(seed)
+    V = desc["vocab"]
+    w = W.make_weights(desc, seed=seed)
+    wn = _f64_weights(W.weights_to_numpy(w))
+    eng = Engine(desc, fuse_weights(w, desc["dtype"], DEV), Bn, int(max(ctx_lens)) + k_max + 1, B_max=Bn,
+                 k_max=k_max, page_perm_seed=perm)
+    od = H.oracle_desc(desc)
+    caches = []
+    for b in range(Bn):
+        kvs = W.context_kv(desc, int(ctx_lens[b]), seed * 100 + b)
+        c = OD.SeqCache(od)
+        c.fill([k.float().numpy() for k, _ in kvs], [v.float().numpy() for _, v in kvs])
+        caches.append(c)
+        if ctx_lens[b] > 0:
+            for l, (k, v) in enumerate(kvs):
+                eng.kv_write(l, b, 0, k.to(DEV), v.to(DEV))
+    eng.ctx_len.copy_(H.dev_i32(ctx_lens))
+    last = rng.integers(0, V, Bn)
+    drafts = rng.integers(0, V, (Bn, k_max))
+    k_b = np.asarray(k_b)
+    blocks = H.pack_rows(last, drafts, k_b)
+    ref_logits = np.concatenate([OD.verify_block(od, wn, caches[b], blocks[b]) for b in range(Bn)])
+    M, Td = int(k_b.sum() + Bn), int(k_b.sum())
+    q_rows = None
+    if q_mode == "dense" and Td > 0:       # proposal: perturbed copy of the target logits at the judged rows
+        rows = np.concatenate([np.arange(k_b[b]) + (k_b[:b].sum() + b) for b in range(Bn)]).astype(int)
+        q_t = torch.tensor(ref_logits[rows] + q_scale * rng.normal(size=(Td, V)), dtype=torch.bfloat16)
+        q_rows = q_t.float().numpy()
+        # make most drafts plausible under q so that accept / reject / bonus all occur
+        for b in range(Bn):
+            for j in range(k_b[b]):
+                if rng.random() < 0.8:
+                    qq = OD.softmax(q_rows[k_b[:b].sum() + j])
+                    drafts[b, j] = rng.choice(V, p=qq)
+        blocks = H.pack_rows(last, drafts, k_b)
+        for c, n in zip(caches, ctx_lens):          # redo the oracle pass with the final drafts
+            c.commit(0)
+        ref_logits = np.concatenate([OD.verify_block(od, wn, caches[b], blocks[b]) for b in range(Bn)])
+    ua, us = W.uniforms(seed + 7, Bn, k_max)
+    slots = H.dev_i32(np.arange(Bn))
+    dt, dl = H.dev_i32(drafts), H.dev_i32(k_b)
+    logits = eng.verify_step(slots, H.dev_i32(last), dt, dl, k_max, want_logits=True)
+    qdev = None if q_rows is None else q_t.to(DEV)
+    out = eng.accept_resample(dt, dl, k_max, H.dev_f32(ua), H.dev_f32(us), q_logits=qdev, temperature=temperature)
+    got = logits.cpu().numpy()[:M]
+    err = np.abs(got - ref_logits).max()
+    assert err <= H.TOL_LOGITS[W.BS_BF16], "logits max-abs %.4g" % err
+    exact, near, res = H.compare_sampler(out, got, drafts, k_b, ua, us, q_rows, temperature)
+    assert near <= max(1, 0.05 * Bn), (exact, near)
+    if check_kv:
+        for b in range(Bn):
+            for l in range(desc["n_layers"]):
+                k, v = eng.kv_read(l, b, int(ctx_lens[b]), int(k_b[b]) + 1)
+                kr, vr = caches[b].k[l][ctx_lens[b]:], caches[b].v[l][ctx_lens[b]:]
+                assert np.abs(k.float().cpu().numpy() - kr).max() <= 2e-2
+                assert np.abs(v.float().cpu().numpy() - vr).max() <= 2e-2
+    n_acc = out["n_accepted"].cpu().numpy()
+    eng.kv_commit(slots, H.dev_i32(n_acc + 1))
+    assert eng.ctx_len.cpu().tolist() == [int(c + n + 1) for c, n in zip(ctx_lens, n_acc)]
+    assert eng.poll_status() == 0
+    stats = dict(err=float(err), exact=exact, near=near, accepted=int(n_acc.sum()), drafts=Td,
+                 emitted=int(out["n_emitted"].sum().item()))
+    print(stats)
+    eng.close()
+    return stats
+
+
+def test_mini_ragged_dense_q():
+    desc = W.shape("mini_bf16")
+    _run_case(desc, ctx_lens=[1, 63, 64, 200, 333, 0, 31, 97], k_b=[8, 0, 3, 8, 5, 2, 1, 7], k_max=8, seed=21)
+
+
+def test_mini_one_hot_and_temperature():
+    desc = W.shape("mini_bf16")
+    _run_case(desc, ctx_lens=[5, 130, 64, 257], k_b=[4, 4, 0, 2], k_max=4, seed=22, temperature=0.7, q_mode="onehot")
+    _run_case(desc, ctx_lens=[5, 130, 64, 257], k_b=[4, 4, 0, 2], k_max=4, seed=23, temperature=0.0, q_mode="dense")
+
+
+def test_mini_wide_groups_k16():
+    """G = 7 query heads per KV head and k up to 16: 119 query rows per KV head (four MFMA row tiles)."""
+    desc = W.shape("mini_bf16", n_q_heads=14, n_kv_heads=2, d_model=320, d_ffn=448, vocab=777)
+    _run_case(desc, ctx_lens=[700, 40, 129, 1000, 3], k_b=[16, 0, 9, 12, 16], k_max=16, seed=24)
+
+
+def test_mini_head_dim_64():
+    desc = W.shape("mini_bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, vocab=4096)
+    _run_case(desc, ctx_lens=[100, 513, 64], k_b=[3, 8, 8], k_max=8, seed=25)
+
+
+def test_slice_1p5b_full_vocab():
+    """Two layers of the 1.5B shape, full 151936 vocabulary, context 2048, k = 8, dense bf16 q."""
+    desc = W.shape("s1p5b", n_layers=2)
+    st = _run_case(desc, ctx_lens=[2048, 2048, 1500, 2048, 17, 2048], k_b=[8, 8, 8, 0, 8, 5], k_max=8, seed=26,
+                   check_kv=False)
+    assert st["accepted"] > 0
+
+
+def test_slice_7b_full_vocab():
+    """Two layers of the 7B shape (G = 7), full 152064 vocabulary, ragged contexts and draft lengths."""
+    desc = W.shape("s7b", n_layers=2)
+    _run_case(desc, ctx_lens=[4096, 512, 1800], k_b=[16, 8, 0], k_max=16, seed=27, check_kv=False, q_mode="onehot")
