@@ -83,7 +83,7 @@ def one_step(wl):
     return out
 
 
-def cpu_baseline(wl, n_seq=1):
+def cpu_baseline(wl, n_seq=8):
     """The oracle, as it stands, on a bounded sample: the first n_seq sequences of the same workload at full depth."""
     from oracle import accept as OA
     from oracle import decoder as OD
@@ -171,7 +171,48 @@ def main():
 
 
 def measure_roofline(wl, args):
-    return {"roofline": None}
+    """Per-kernel-class durations measured live with HIP events on the step's own stream (the library's
+    bs_profile_* hooks), one pass of `steps` steps per class, after the timed region.  The dominant class is
+    reported against its roofline: achieved = ALGORITHMIC bytes (or flops) per launch / mean launch duration."""
+    eng, desc = wl["eng"], wl["desc"]
+    Bn, k, ctx = wl["B"], wl["k"], wl["ctx"]
+    M = Bn * (k + 1)
+    d, Hq, Hkv, D, F, V = (desc["d_model"], desc["n_q_heads"], desc["n_kv_heads"], desc["head_dim"], desc["d_ffn"],
+                           desc["vocab"])
+    kv_bytes_per_token_layer = 2 * Hkv * D * 2                      # K and V rows of one layer, bf16
+    algo = {   # class: (bound, units per launch)  units = bytes for hbm, flops for mfma
+        "attention": ("hbm", kv_bytes_per_token_layer * Bn * (ctx + k + 1)),
+        "gemm_qkv": ("mfma", 2.0 * M * (Hq + 2 * Hkv) * D * d),
+        "gemm_o": ("mfma", 2.0 * M * d * Hq * D),
+        "gemm_gate_up": ("mfma", 2.0 * M * 2 * F * d),
+        "gemm_down": ("mfma", 2.0 * M * d * F),
+        "lmhead": ("mfma", 2.0 * M * V * d),
+    }
+    per_class = {}
+    for name, cls in B.PROF_CLASSES.items():
+        B.bs_profile_begin(eng.ctx, cls)
+        for _ in range(args.steps):
+            one_step(wl)
+        ms, n = B.bs_profile_end(eng.ctx)
+        if n:
+            per_class[name] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps,
+                                   us_per_launch=1e3 * ms / n)
+    dom = max((c for c in per_class if c in algo), key=lambda c: per_class[c]["ms_per_step"])
+    bound, units = algo[dom]
+    sec = per_class[dom]["us_per_launch"] * 1e-6
+    if bound == "hbm":
+        achieved, peak, unit = units / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = units / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+    for c, (bnd, u) in algo.items():
+        if c in per_class:
+            t = per_class[c]["us_per_launch"] * 1e-6
+            per_class[c]["bound"] = bnd
+            per_class[c]["frac_of_peak"] = (u / t / 1e9 / HBM_PEAK_GBS) if bnd == "hbm" else (u / t / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+    return {"roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                         "frac": achieved / peak, "traffic": None,
+                         "us_per_launch": per_class[dom]["us_per_launch"]},
+            "kernel_classes": per_class}
 
 
 if __name__ == "__main__":

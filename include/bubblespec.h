@@ -87,7 +87,9 @@ typedef struct {
  * inside a page is private to the library (it is the MFMA operand order for bf16); use
  * bs_kv_write / bs_kv_read to move dense rows in and out.
  *   block_table[slot][j] = page id of tokens [j*64, j*64+64) of that slot (same id in all layers)
- *   ctx_len[slot]        = committed length c of the slot; advanced only by bs_kv_commit. */
+ *   ctx_len[slot]        = committed length c of the slot; advanced only by bs_kv_commit.
+ * Pages must hold finite values before first use (zero-fill them once): positions beyond a row's
+ * causal limit enter the P*V product with weight exactly 0, and 0 * NaN would still poison it. */
 typedef struct {
   int32_t n_pages, n_slots, max_pages_per_seq;
   void* const* k_pages;   /* host[L] -> dev [n_pages] pages */
@@ -102,8 +104,11 @@ typedef struct bs_ctx bs_ctx;
 size_t bs_workspace_bytes(const bs_model_desc* desc, int B_max, int k_max);
 
 /* Creates the host-side context.  `workspace` (dev, 256-byte aligned, >= bs_workspace_bytes)
- * stays owned by the caller and must outlive the context.  Enqueues a clear of the device status
- * word on `stream`.  Errors: BS_EINVAL (null / bad dtype), BS_ESHAPE (unsupported shape: head_dim
+ * stays owned by the caller and must outlive the context.  Enqueues on `stream` a clear of the
+ * device status word and, for bf16 models, a one-time re-pack of the projection and LM-head
+ * matrices into the workspace (float16, matrix-unit operand order); after that work has finished
+ * the library no longer reads wqkv / wo / w_gate_up / w_down / lm_head (embed and the norm gains
+ * are still read in place).  Errors: BS_EINVAL (null / bad dtype), BS_ESHAPE (unsupported shape: head_dim
  * not in {64,128}, d_model or d_ffn not a multiple of 64, Hq % Hkv != 0, k_max > BS_MAX_K, ...),
  * BS_ECAPACITY (workspace too small). */
 bs_status bs_create(const bs_model_desc* desc, const bs_weights* weights, const bs_kv_desc* kv,
@@ -192,6 +197,26 @@ bs_status bs_kv_write(bs_ctx* ctx, int layer, int slot, int pos0, int n, const v
                       const void* v_rows, void* stream);
 bs_status bs_kv_read(bs_ctx* ctx, int layer, int slot, int pos0, int n, void* k_rows, void* v_rows,
                      void* stream);
+
+/* Measurement hooks (not part of Alg. 1): time every launch of one kernel class of the following
+ * bs_verify_step / bs_accept_resample calls with HIP events recorded on the call's own stream.
+ * bs_profile_begin selects the class (BS_PROF_*) and clears the counters; bs_profile_end synchronises
+ * `stream` and returns the summed duration in milliseconds and the number of launches, then switches
+ * the hooks off.  At most 4096 launches are timed per begin/end pair; later ones run untimed.
+ * Errors: BS_EINVAL (null, unknown class), BS_EHIP. */
+enum {
+  BS_PROF_NONE = 0,
+  BS_PROF_ATTENTION = 1,   /* ragged verify attention (bf16 models: the MFMA kernel, merge excluded) */
+  BS_PROF_GEMM_QKV = 2,
+  BS_PROF_GEMM_O = 3,
+  BS_PROF_GEMM_GATE_UP = 4,
+  BS_PROF_GEMM_DOWN = 5,
+  BS_PROF_LMHEAD = 6,      /* LM-head GEMM with the softmax-statistics epilogue */
+  BS_PROF_SAMPLE = 7,      /* residual / bonus inverse-CDF sampling */
+  BS_PROF_LOOKUP = 8       /* draft lookup */
+};
+bs_status bs_profile_begin(bs_ctx* ctx, int kernel_class);
+bs_status bs_profile_end(bs_ctx* ctx, void* stream, float* total_ms /*host*/, int* launches /*host*/);
 
 /* Synchronises `stream`, returns the device status word (BS_FAULT_* bits) and clears it. */
 bs_status bs_poll_status(bs_ctx* ctx, void* stream, int32_t* fault_out /*host*/);

@@ -18,7 +18,9 @@ STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", 
 
 EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs_pool_bind", "bs_draft_lookup",
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
-           "bs_kv_read", "bs_poll_status"]
+           "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end"]
+PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
+                "sample": 7, "lookup": 8}
 
 
 class bs_model_desc(C.Structure):
@@ -70,6 +72,8 @@ def lib():
         L.bs_kv_write.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.bs_kv_read.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.bs_poll_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
+        L.bs_profile_begin.argtypes = [vp, i32]
+        L.bs_profile_end.argtypes = [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         for name in EXPORTS:
             if name not in ("bs_workspace_bytes", "bs_destroy", "bs_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -187,3 +191,13 @@ def bs_poll_status(ctx):
     out = C.c_int32(0)
     _check(ctx, lib().bs_poll_status(ctx, _stream(), C.byref(out)))
     return out.value
+
+
+def bs_profile_begin(ctx, kernel_class):
+    _check(ctx, lib().bs_profile_begin(ctx, kernel_class))
+
+
+def bs_profile_end(ctx):
+    ms, n = C.c_float(0), C.c_int(0)
+    _check(ctx, lib().bs_profile_end(ctx, _stream(), C.byref(ms), C.byref(n)))
+    return ms.value, n.value

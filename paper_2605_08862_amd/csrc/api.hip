@@ -34,6 +34,11 @@ struct bs_ctx {
   const int32_t* pool_tokens = nullptr;
   const int64_t* rollout_offsets = nullptr;
   const int32_t* prompt_rollout_begin = nullptr;
+  // measurement hooks
+  int prof_class = 0;
+  std::vector<hipEvent_t> prof_ev;     // pairs (start, stop), created on first use
+  size_t prof_used = 0;
+  hipEvent_t prof_pending_stop = nullptr;
   // state
   bool verify_pending = false;
   int last_B = 0, last_k_max = 0;
@@ -137,6 +142,26 @@ bs_status fail(bs_ctx* c, bs_status st, const char* msg) {
   return st;
 }
 
+// RAII-less helper: records an event pair around one launch when its class is being profiled.
+struct ProfScope {
+  bs_ctx* c; hipStream_t st; bool on; hipEvent_t stop;
+  ProfScope(bs_ctx* c_, int cls, hipStream_t st_) : c(c_), st(st_), on(false), stop(nullptr) {
+    if (c->prof_class != cls || c->prof_used + 2 > 8192) return;
+    if (c->prof_ev.size() < c->prof_used + 2) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+      c->prof_ev.push_back(a);
+      c->prof_ev.push_back(b);
+    }
+    hipEvent_t start = c->prof_ev[c->prof_used];
+    stop = c->prof_ev[c->prof_used + 1];
+    c->prof_used += 2;
+    (void)hipEventRecord(start, st);
+    on = true;
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(stop, st); }
+};
+
 bs_status check_hip(bs_ctx* c) {
   hipError_t e = hipGetLastError();
   if (e == hipSuccess) return BS_OK;
@@ -145,6 +170,19 @@ bs_status check_hip(bs_ctx* c) {
 }
 
 }  // namespace
+
+// Called by launch_attention around its main kernel when attention is the profiled class.
+void attention_prof_mark(void* token, hipStream_t st, bool begin) {
+  bs_ctx* c = (bs_ctx*)token;
+  if (begin) {
+    ProfScope s(c, BS_PROF_ATTENTION, st);
+    c->prof_pending_stop = s.on ? s.stop : nullptr;
+    s.on = false;                       // the stop event is recorded by the matching end mark
+  } else if (c->prof_pending_stop) {
+    (void)hipEventRecord(c->prof_pending_stop, st);
+    c->prof_pending_stop = nullptr;
+  }
+}
 
 extern "C" {
 
@@ -214,7 +252,35 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   return BS_OK;
 }
 
-void bs_destroy(bs_ctx* ctx) { delete ctx; }
+void bs_destroy(bs_ctx* ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+bs_status bs_profile_begin(bs_ctx* c, int kernel_class) {
+  if (!c) return BS_EINVAL;
+  if (kernel_class < BS_PROF_NONE || kernel_class > BS_PROF_LOOKUP) return fail(c, BS_EINVAL, "bs_profile_begin: unknown class");
+  c->prof_class = kernel_class;
+  c->prof_used = 0;
+  return BS_OK;
+}
+
+bs_status bs_profile_end(bs_ctx* c, void* stream, float* total_ms, int* launches) {
+  if (!c || !total_ms || !launches) return BS_EINVAL;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return check_hip(c);
+  float tot = 0.f;
+  for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]) != hipSuccess) return check_hip(c);
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = (int)(c->prof_used / 2);
+  c->prof_class = BS_PROF_NONE;
+  c->prof_used = 0;
+  return BS_OK;
+}
 
 const char* bs_last_error(const bs_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
@@ -239,6 +305,7 @@ bs_status bs_draft_lookup(bs_ctx* c, int B, const int32_t* seq_prompt, const int
   if (B < 1 || B > c->B_max || k_max < 0 || k_max > c->k_max || max_match < 1 || max_match > 8 || min_match < 1 ||
       min_match > max_match)
     return fail(c, BS_ESHAPE, "bs_draft_lookup: B, k_max or match lengths out of range");
+  ProfScope ps(c, BS_PROF_LOOKUP, (hipStream_t)stream);
   launch_lookup(B, c->n_prompts, c->pool_tokens, c->rollout_offsets, c->prompt_rollout_begin, seq_prompt, tail_tokens,
                 max_match, min_match, k_max, draft_tokens, draft_len, (hipStream_t)stream);
   return check_hip(c);
@@ -260,13 +327,18 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   launch_embed(s, p, M_max, c->embed, c->h, st);
   for (int l = 0; l < s.L; ++l) {
     launch_rmsnorm(s, p, M_max, c->h, c->attn_norm[l], c->a, st);
-    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st);
+    { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
+      launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st); }
     launch_rope_append(s, p, c->kv, M_max, c->qkv, c->q, c->k_pages[l], c->v_pages[l], st);
-    launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch, st);
-    launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l], c->h, st);
+    launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
+                     c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
+    { ProfScope ps(c, BS_PROF_GEMM_O, st);
+      launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l], c->h, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->mlp_norm[l], c->a, st);
-    launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st);
-    launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l], c->h, st);
+    { ProfScope ps(c, BS_PROF_GEMM_GATE_UP, st);
+      launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st); }
+    { ProfScope ps(c, BS_PROF_GEMM_DOWN, st);
+      launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l], c->h, st); }
   }
   launch_rmsnorm(s, p, M_max, c->h, c->final_norm, c->hf, st);
   if (logits_debug && s.dtype == BS_F32)
@@ -304,7 +376,8 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
     n_vtiles = (V + 1023) / 1024;
     sample_base = c->full_logits;
   } else {
-    launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, inv_temp, c->sb, nullptr, st);
+    { ProfScope ps(c, BS_PROF_LMHEAD, st);
+      launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, inv_temp, c->sb, nullptr, st); }
     n_vtiles = (V + 63) / 64;
     sample_base = c->sb.sel_logits;
     rows_selected = true;
@@ -314,6 +387,7 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
                      n_accepted, out_tokens, n_emitted, near_tie, st);
   if (temperature > 0.f) {
     if (rows_selected) launch_lmhead_rows(s, B, c->hf, c->lm_head, c->sb, st);
+    ProfScope ps(c, BS_PROF_SAMPLE, st);
     launch_sample(B, k_max, V, sample_base, rows_selected, q_logits, q_dtype, temperature, u_sample, c->sb, n_accepted,
                   out_tokens, n_emitted, near_tie, st);
   }

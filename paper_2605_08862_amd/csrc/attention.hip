@@ -316,7 +316,7 @@ size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max) {
 template <int NQ, int QG, int D>
 static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int B, int M_max, const void* q,
                              const void* k_pages, const void* v_pages, void* out, void* scratch, int n_split,
-                             hipStream_t st) {
+                             void* prof_token, hipStream_t st) {
   constexpr int RP = 32 * NQ * QG;
   const size_t lds = (size_t)RP * (D + 4) * 4 + 2 * 4 * 32 * NQ * 4;
   float* part_ml = (float*)scratch;
@@ -325,15 +325,18 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
   auto kern = attn_mfma_kernel<NQ, QG, D>;
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
+  if (prof_token) attention_prof_mark(prof_token, st, true);
   hipLaunchKernelGGL(kern, dim3(s.Hkv, B, n_split), dim3(256), lds, st, p, kv, s.Hq, s.Hkv, scale_log2e,
                      (const f16*)q, (const bf16*)k_pages, (const bf16*)v_pages, (f16*)out, part_o, part_ml, n_split);
+  if (prof_token) attention_prof_mark(prof_token, st, false);
   if (n_split > 1)
     hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, RP, part_o, part_ml,
                        n_split, (f16*)out);
 }
 
 void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
-                      const void* k_pages, const void* v_pages, void* out, void* scratch, hipStream_t st) {
+                      const void* k_pages, const void* v_pages, void* out, void* scratch, void* prof_token,
+                      hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)s.D);
   static const bool force_simple = getenv("BS_SIMPLE_ATTN") != nullptr;   // debugging aid
   if (s.dtype == BS_F32) {
@@ -352,8 +355,8 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
   const int tiles = (rows_padded(s, k_max)) / 32;
 #define BS_ATTN(NQ, QG)                                                                                         \
   do {                                                                                                          \
-    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, st); \
-    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, st);   \
+    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, prof_token, st); \
+    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, prof_token, st);   \
   } while (0)
   if (tiles == 1) BS_ATTN(1, 1);
   else if (tiles == 2) BS_ATTN(2, 1);

@@ -115,7 +115,9 @@ size_t packed_weight_elems(int N, int K);
 void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st);
 // attention.hip
 void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
-                      const void* k_pages, const void* v_pages, void* out, void* scratch, hipStream_t st);
+                      const void* k_pages, const void* v_pages, void* out, void* scratch, void* prof_token,
+                      hipStream_t st);
+void attention_prof_mark(void* token, hipStream_t st, bool begin);   // api.hip: event pair around the main kernel
 size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
 // sampler.hip
 struct SamplerBufs {
