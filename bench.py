@@ -35,12 +35,13 @@ def build_workload(args):
     Bn, ctx, k = args.batch, args.context, args.k
     w = W.make_weights(desc, seed=1002, device=dev)
     eng = Engine(desc, fuse_weights(w, desc["dtype"], dev), Bn, ctx + 2 * k + 2, B_max=Bn, k_max=k)
-    # committed context: K, V ~ N(0, (0.02 sqrt(d))^2); pages are a permutation of i.i.d. values, fill them in place
+    # committed context: K, V ~ N(0, (0.02 sqrt(d))^2) rounded to bf16; pages are a permutation of i.i.d. values,
+    # so they are filled in place (page encoding of bf16 models: the bf16 value as float16 bits)
     g = torch.Generator(device=dev).manual_seed(2002)
     s = 0.02 * desc["d_model"] ** 0.5
     for l in range(desc["n_layers"]):
-        eng.k_pages[l].copy_((torch.randn(eng.k_pages[l].shape, generator=g, device=dev) * s).to(torch.bfloat16))
-        eng.v_pages[l].copy_((torch.randn(eng.v_pages[l].shape, generator=g, device=dev) * s).to(torch.bfloat16))
+        eng.k_pages[l].copy_((torch.randn(eng.k_pages[l].shape, generator=g, device=dev) * s).to(torch.bfloat16).to(torch.float16))
+        eng.v_pages[l].copy_((torch.randn(eng.v_pages[l].shape, generator=g, device=dev) * s).to(torch.bfloat16).to(torch.float16))
     eng.ctx_len.fill_(ctx)
     slots = torch.arange(Bn, dtype=torch.int32, device=dev)
     last = torch.randint(0, desc["vocab"], (Bn,), generator=g, device=dev, dtype=torch.int32)

@@ -83,9 +83,10 @@ typedef struct {
 } bs_weights;
 
 /* Paged KV cache.  A page holds BS_PAGE_TOKENS tokens of one layer for all KV heads.  The page
- * byte size is Hkv * BS_PAGE_TOKENS * D * sizeof(dtype), for K and for V.  The element order
- * inside a page is private to the library (it is the MFMA operand order for bf16); use
- * bs_kv_write / bs_kv_read to move dense rows in and out.
+ * byte size is Hkv * BS_PAGE_TOKENS * D * sizeof(dtype), for K and for V.  Element order and
+ * encoding inside a page are private to the library (bf16 models: matrix-unit operand order, each
+ * bf16-rounded value held as IEEE float16 bits, which is exact for 6.1e-5 <= |x| <= 65504); use
+ * bs_kv_write / bs_kv_read to move dense rows (in desc.dtype) in and out.
  *   block_table[slot][j] = page id of tokens [j*64, j*64+64) of that slot (same id in all layers)
  *   ctx_len[slot]        = committed length c of the slot; advanced only by bs_kv_commit.
  * Pages must hold finite values before first use (zero-fill them once): positions beyond a row's

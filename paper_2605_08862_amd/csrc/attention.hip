@@ -12,8 +12,8 @@
 //     load is one contiguous 1 KiB read that lands directly in the operand registers: no LDS
 //     staging, no bank conflicts, no shuffles.  LDS is used only for the final cross-wave merge.
 //   * Arithmetic runs on the f16 MFMA: queries and probabilities carry 11 significant bits (with
-//     8-bit bf16 queries the logits of the 7B-shape slice drift by 3e-2); the bf16 K/V fragments are
-//     widened to float16 in registers (exact for 6.1e-5 <= |x| <= 65504) right before use.
+//     8-bit bf16 queries the logits of the 7B-shape slice drift by 3e-2).  The cache holds
+//     bf16-rounded K/V values in float16 encoding, so page data are MFMA operands as they are.
 //   * S^T = K Q^T (tokens are accumulator rows, the lane is the query row), so the softmax
 //     statistics of a query row are lane-private apart from one exchange between the two lane
 //     halves, and the probabilities are already laid out as the B operand of O^T = V^T P^T.
@@ -31,19 +31,6 @@ __device__ __forceinline__ f16x8 pack_f16x8(const float* v) {
   for (int j = 0; j < 8; ++j) r[j] = (f16)v[j];
   return r;
 }
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-// eight bf16 (packed in four dwords) -> eight float16; three VALU ops per pair
-__device__ __forceinline__ f16x8 widen_bf16x8(u32x4 v) {
-  f16x8 r;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float lo = __uint_as_float(v[j] << 16), hi = __uint_as_float(v[j] & 0xffff0000u);
-    const f16x2 pr = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(lo, hi));   // exact: no rounding occurs
-    r[2 * j] = pr[0];
-    r[2 * j + 1] = pr[1];
-  }
-  return r;
-}
 }  // namespace
 
 // NQ: query-row tiles (of 32) handled by one wave; QG: groups of waves, each group owning NQ of the
@@ -52,18 +39,18 @@ __device__ __forceinline__ f16x8 widen_bf16x8(u32x4 v) {
 // RP = 32*NQ*QG.
 template <int NQ, int QG, int D>
 __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int Hq, int Hkv, float scale_log2e,
-                                                        const f16* __restrict__ q, const bf16* __restrict__ k_pages,
-                                                        const bf16* __restrict__ v_pages, f16* __restrict__ out,
+                                                        const f16* __restrict__ q, const f16* __restrict__ k_pages,
+                                                        const f16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
                                                         int n_split) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product
   constexpr int DT = D / 32;            // 32-wide d tiles of the output
   constexpr int RP = 32 * NQ * QG;      // padded query rows per workgroup
   constexpr int WPG = 4 / QG;           // waves per group (token split inside the workgroup)
-  constexpr int DS = D + 4;             // LDS row stride of the merged accumulator (bank spread)
+  constexpr int SLOT = NQ * DT * 16 * 64;               // floats of one wave's output accumulator
   extern __shared__ __align__(16) char lds_raw[];
-  float* s_o = (float*)lds_raw;                         // [RP][DS] merged output accumulator
-  float* s_m = s_o + RP * DS;                           // [4][32*NQ] per-wave running max
+  float* s_o = (float*)lds_raw;                         // [2 slots][SLOT] accumulators in flight during the merge
+  float* s_m = s_o + 2 * SLOT;                          // [4][32*NQ] per-wave running max
   float* s_l = s_m + 4 * 32 * NQ;                       // [4][32*NQ] per-wave sum
 
   const int h = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
@@ -73,31 +60,58 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
   const int c = p.seq_c[b];
   const int n_tok = c + k + 1;
   const int R = (k + 1) * G;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the wave index is made scalar so that everything derived from it (tile index, block-table lookups)
+  // stays on the scalar unit: a vector load of a page id inside the loop would force vmcnt(0) and
+  // serialise the K/V prefetch
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int grp = wave / WPG, wig = wave % WPG;
   const int ln = lane & 31, lg = lane >> 5;
   const int row0 = p.row_start[b];
   const int32_t* bt = kv.block_table + (size_t)p.seq_slot[b] * kv.max_pages;
   const size_t page_elems = kv_page_elems(Hkv, D);
 
-  // query fragments (B operand): lane (n, g) holds Q[row n][g*D/2 + 8s + j]
-  u32x4 qf[NQ][KS];
+  // Query fragments (B operand: lane (n, g) holds Q[row n][g*D/2 + 8s + j]) are staged once in LDS in
+  // fragment order and re-read per use: keeping them in registers would push the kernel into spills,
+  // and a spill reload inside the loop forces vmcnt(0), i.e. it serialises the K/V prefetch.
+  u32x4* s_q = (u32x4*)lds_raw;                         // [RP/32][KS][64] (aliases s_o; dead before the merge)
   int lim[NQ];                                          // last visible cache position of the lane's row
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
     const int qr = (grp * NQ + qt) * 32 + ln;
+    lim[qt] = (qr < R) ? c + qr / G : -1;
+  }
+  const int n_tiles = (n_tok + kTile - 1) / kTile;
+  const int tps = (n_tiles + n_split - 1) / n_split;
+  const int t_begin = split * tps, t_end = min(t_begin + tps, n_tiles);
+  const bool group_active = (grp * NQ * 32) < R;        // wave-uniform
+  auto load_tile = [&](int t, u32x4 (&kf)[KS], u32x4 (&vf)[DT * 2]) {
+    const int tb = t * kTile;
+    const int page = min(max(bt[tb / kPage], 0), kv.n_pages - 1);
+    const size_t off = (size_t)page * page_elems + (size_t)(h * 2 + ((tb / kTile) & 1)) * (kTile * D) + lane * 8;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kf[s] = *(const u32x4*)(k_pages + off + s * 512);
+#pragma unroll
+    for (int x = 0; x < DT * 2; ++x) vf[x] = *(const u32x4*)(v_pages + off + x * 512);
+  };
+  // register double buffering; the first tile is requested before the queries are staged so that its
+  // latency overlaps that work
+  u32x4 ka[KS], va[DT * 2], kb[KS], vb[DT * 2];
+  int t = t_begin + wig;
+  if (group_active && t < t_end) load_tile(t, ka, va);
+
+  for (int f = wave; f < (RP / 32) * KS; f += 4) {      // one fragment (1 KiB) per wave iteration
+    const int qtile = f / KS, s = f % KS;
+    const int qr = qtile * 32 + ln;
+    u32x4 v = u32x4{0, 0, 0, 0};
     if (qr < R) {
       const int iq = qr / G, hg = qr % G;
-      const f16* qp = q + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + lg * (D / 2);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) qf[qt][s] = *(const u32x4*)(qp + s * 8);
-      lim[qt] = c + iq;
-    } else {
-#pragma unroll
-      for (int s = 0; s < KS; ++s) qf[qt][s] = u32x4{0, 0, 0, 0};
-      lim[qt] = -1;
+      v = *(const u32x4*)(q + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + lg * (D / 2) + s * 8);
     }
+    s_q[f * 64 + lane] = v;
   }
+  __syncthreads();
+  const u32x4* my_q = s_q + (size_t)(grp * NQ) * KS * 64 + lane;
+
   f32x16 o[NQ][DT];
   float m_run[NQ], l_run[NQ];
 #pragma unroll
@@ -110,98 +124,84 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
       for (int i = 0; i < 16; ++i) o[qt][dt][i] = 0.f;
   }
 
-  const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int tps = (n_tiles + n_split - 1) / n_split;
-  const int t_begin = split * tps, t_end = min(t_begin + tps, n_tiles);
-  const bool group_active = (grp * NQ * 32) < R;        // wave-uniform
-
-  auto tile_ptrs = [&](int t, const bf16*& kp, const bf16*& vp) {
-    const int tb = t * kTile;
-    const int page = min(max(bt[tb / kPage], 0), kv.n_pages - 1);
-    const size_t off = (size_t)page * page_elems + (size_t)(h * 2 + ((tb / kTile) & 1)) * (kTile * D) + lane * 8;
-    kp = k_pages + off;
-    vp = v_pages + off;
+  auto compute_tile = [&](int t, const u32x4 (&kc)[KS], const u32x4 (&vc)[DT * 2]) {
+    const int tok0 = t * kTile + 16 * lg;               // accumulator register i <-> token tok0 + i
+    const bool full = (t + 1) * kTile - 1 <= c;         // every token visible to every row: no masking
+    f32x16 st[NQ];
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st[qt][i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const f16x8 kh = as_f16x8(kc[s]);
+#pragma unroll
+      for (int qt = 0; qt < NQ; ++qt)
+        st[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, as_f16x8(my_q[(qt * KS + s) * 64]), st[qt], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f16x8 pf[NQ][2];
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
+      float x[16];
+      if (full) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = st[qt][i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = (tok0 + i <= lim[qt]) ? st[qt][i] : -INFINITY;
+      }
+      float mloc = x[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, x[i]);
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * scale_log2e;       // scale > 0 commutes with max
+      const float m_new = fmaxf(m_run[qt], mloc);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        x[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], scale_log2e, -m_safe));   // exp2(-inf) = 0
+        psum += x[i];
+      }
+      l_run[qt] = l_run[qt] * alpha + psum;             // per lane half; halves are added at the end
+      m_run[qt] = m_new;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[qt][dt][i] *= alpha;
+      }
+      pf[qt][0] = pack_f16x8(x);
+      pf[qt][1] = pack_f16x8(x + 8);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        const f16x8 vh = as_f16x8(vc[dt * 2 + t2]);
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt)
+          o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, pf[qt][t2], o[qt][dt], 0, 0, 0);
+      }
   };
 
   if (group_active) {
-    u32x4 kf[KS], vf[DT * 2];
-    int t = t_begin + wig;
-    if (t < t_end) {
-      const bf16 *kp, *vp;
-      tile_ptrs(t, kp, vp);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) kf[s] = *(const u32x4*)(kp + s * 512);
-#pragma unroll
-      for (int x = 0; x < DT * 2; ++x) vf[x] = *(const u32x4*)(vp + x * 512);
-    }
     for (; t < t_end; t += WPG) {
-      u32x4 kc[KS], vc[DT * 2];
+      // current tile -> kb/vb (register moves), next tile requested into ka/va, then compute: the
+      // loads of tile t+WPG are in flight during the whole computation of tile t
 #pragma unroll
-      for (int s = 0; s < KS; ++s) kc[s] = kf[s];
+      for (int s = 0; s < KS; ++s) kb[s] = ka[s];
 #pragma unroll
-      for (int x = 0; x < DT * 2; ++x) vc[x] = vf[x];
-      if (t + WPG < t_end) {                            // prefetch the wave's next tile
-        const bf16 *kp, *vp;
-        tile_ptrs(t + WPG, kp, vp);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kf[s] = *(const u32x4*)(kp + s * 512);
-#pragma unroll
-        for (int x = 0; x < DT * 2; ++x) vf[x] = *(const u32x4*)(vp + x * 512);
-      }
-      const int tok0 = t * kTile + 16 * lg;             // accumulator register i <-> token tok0 + i
-      f32x16 st[NQ];
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st[qt][i] = 0.f;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const f16x8 kh = widen_bf16x8(kc[s]);
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt)
-          st[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, as_f16x8(qf[qt][s]), st[qt], 0, 0, 0);
-      }
-      f16x8 pf[NQ][2];
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        float x[16];
-        float mloc = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          x[i] = (tok0 + i <= lim[qt]) ? st[qt][i] * scale_log2e : -INFINITY;
-          mloc = fmaxf(mloc, x[i]);
-        }
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_run[qt], mloc);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m_run[qt] - m_safe);
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { x[i] = exp2f(x[i] - m_safe); psum += x[i]; }
-        l_run[qt] = l_run[qt] * alpha + psum;           // per lane half; halves are added at the end
-        m_run[qt] = m_new;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[qt][dt][i] *= alpha;
-        }
-        pf[qt][0] = pack_f16x8(x);
-        pf[qt][1] = pack_f16x8(x + 8);
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-          const f16x8 vh = widen_bf16x8(vc[dt * 2 + t2]);
-#pragma unroll
-          for (int qt = 0; qt < NQ; ++qt)
-            o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, pf[qt][t2], o[qt][dt], 0, 0, 0);
-        }
+      for (int x = 0; x < DT * 2; ++x) vb[x] = va[x];
+      if (t + WPG < t_end) load_tile(t + WPG, ka, va);
+      compute_tile(t, kb, vb);
     }
   }
+  __syncthreads();                                      // all waves are done with s_q before s_o reuses it
 
-  // ---- merge the waves of each group -------------------------------------------------------
+  // ---- merge the waves of each group (tree, accumulators cross LDS in register order) --------
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
     l_run[qt] += __shfl_xor(l_run[qt], 32);
@@ -211,7 +211,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
     }
   }
   __syncthreads();
-  float m_tot[NQ], l_tot[NQ], f_own[NQ];
+  float m_tot[NQ], l_tot[NQ];
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
     float mt = -INFINITY;
@@ -226,51 +226,79 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
     }
     m_tot[qt] = mt;
     l_tot[qt] = lt;
-    f_own[qt] = exp2f(m_run[qt] - ms);
-  }
-  for (int w = 0; w < WPG; ++w) {                       // deterministic order: wave 0 stores, others add
-    if (wig == w) {
+    const float f_own = exp2f(m_run[qt] - ms);
 #pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        float* dst = s_o + (size_t)((grp * NQ + qt) * 32 + ln) * DS;
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[qt][dt][i] *= f_own;
+  }
+  // slot of a group: QG == 1 uses both slots in the first round, QG == 2 one slot per group
+  auto put = [&](float* slot) {
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          *(f32x4*)(slot + (((qt * DT + dt) * 4 + i4) * 64 + lane) * 4) =
+              f32x4{o[qt][dt][4 * i4], o[qt][dt][4 * i4 + 1], o[qt][dt][4 * i4 + 2], o[qt][dt][4 * i4 + 3]};
+  };
+  auto add = [&](const float* slot) {
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 v = *(const f32x4*)(slot + (((qt * DT + dt) * 4 + i4) * 64 + lane) * 4);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[qt][dt][4 * i4 + j] += v[j];
+        }
+  };
+  if (WPG == 4) {
+    if (wig >= 2) put(s_o + (wig - 2) * SLOT);
+    __syncthreads();
+    if (wig < 2) add(s_o + wig * SLOT);
+    __syncthreads();
+    if (wig == 1) put(s_o);
+    __syncthreads();
+    if (wig == 0) add(s_o);
+  } else {
+    if (wig == 1) put(s_o + grp * SLOT);
+    __syncthreads();
+    if (wig == 0) add(s_o + grp * SLOT);
+  }
+
+  // ---- write from registers (first wave of each group): final rows or split partials -------------
+  if (wig == 0) {
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
+      const int qr = (grp * NQ + qt) * 32 + ln;
+      if (qr >= R) continue;
+      const int iq = qr / G, hg = qr % G;
+      if (n_split == 1) {
+        const float inv = 1.0f / l_tot[qt];
+        f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int d = dt * 32 + acc_row(lane, i);
-            const float v = o[qt][dt][i] * f_own[qt];
-            if (w == 0) dst[d] = v; else dst[d] += v;
+          for (int i4 = 0; i4 < 4; ++i4) {
+            typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+            f16x4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (f16)(o[qt][dt][4 * i4 + j] * inv);
+            *(f16x4*)(dst + dt * 32 + 8 * i4 + 4 * lg) = v;
           }
+      } else {
+        const size_t pr = (((size_t)b * Hkv + h) * n_split + split) * RP + qr;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4)
+            *(f32x4*)(part_o + pr * D + dt * 32 + 8 * i4 + 4 * lg) =
+                f32x4{o[qt][dt][4 * i4], o[qt][dt][4 * i4 + 1], o[qt][dt][4 * i4 + 2], o[qt][dt][4 * i4 + 3]};
+        if (lg == 0) { part_ml[pr * 2] = m_tot[qt]; part_ml[pr * 2 + 1] = l_tot[qt]; }
       }
-    }
-    __syncthreads();
-  }
-  if (wig == 0 && lg == 0) {                            // publish the group's totals for the writers
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      s_m[(grp * WPG) * 32 * NQ + qt * 32 + ln] = m_tot[qt];
-      s_l[(grp * WPG) * 32 * NQ + qt * 32 + ln] = l_tot[qt];
-    }
-  }
-  __syncthreads();
-
-  // ---- write: final rows (n_split == 1) or partials ------------------------------------------
-  for (int idx = threadIdx.x; idx < RP * (D / 4); idx += 256) {
-    const int qr = idx / (D / 4), d4 = (idx % (D / 4)) * 4;
-    if (qr >= R) continue;
-    const int g2 = qr / (32 * NQ), qt = (qr / 32) % NQ, n = qr % 32;
-    const float mt = s_m[(g2 * WPG) * 32 * NQ + qt * 32 + n], lt = s_l[(g2 * WPG) * 32 * NQ + qt * 32 + n];
-    const float* src = s_o + (size_t)qr * DS + d4;
-    if (n_split == 1) {
-      const int iq = qr / G, hg = qr % G;
-      const float inv = 1.0f / lt;
-      f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + d4;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) dst[j] = (f16)(src[j] * inv);
-    } else {
-      const size_t pr = (((size_t)b * Hkv + h) * n_split + split) * RP + qr;
-      *(f32x4*)(part_o + pr * D + d4) = *(const f32x4*)src;
-      if (d4 == 0) { part_ml[pr * 2] = mt; part_ml[pr * 2 + 1] = lt; }
     }
   }
 }
@@ -318,7 +346,7 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
                              const void* k_pages, const void* v_pages, void* out, void* scratch, int n_split,
                              void* prof_token, hipStream_t st) {
   constexpr int RP = 32 * NQ * QG;
-  const size_t lds = (size_t)RP * (D + 4) * 4 + 2 * 4 * 32 * NQ * 4;
+  const size_t lds = (size_t)2 * NQ * (D / 32) * 16 * 64 * 4 + 2 * 4 * 32 * NQ * 4;   // two accumulator slots + statistics (>= the query fragments)
   float* part_ml = (float*)scratch;
   float* part_o = part_ml + (size_t)B * s.Hkv * n_split * RP * 2;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
@@ -327,7 +355,7 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
   if (prof_token) attention_prof_mark(prof_token, st, true);
   hipLaunchKernelGGL(kern, dim3(s.Hkv, B, n_split), dim3(256), lds, st, p, kv, s.Hq, s.Hkv, scale_log2e,
-                     (const f16*)q, (const bf16*)k_pages, (const bf16*)v_pages, (f16*)out, part_o, part_ml, n_split);
+                     (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, n_split);
   if (prof_token) attention_prof_mark(prof_token, st, false);
   if (n_split > 1)
     hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, RP, part_o, part_ml,
@@ -345,12 +373,12 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
     return;
   }
   if (force_simple) {
-    hipLaunchKernelGGL((attn_simple_kernel<bf16, f16>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
-                       (const f16*)q, (const bf16*)k_pages, (const bf16*)v_pages, (f16*)out);
+    hipLaunchKernelGGL((attn_simple_kernel<f16, f16>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
+                       (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out);
     return;
   }
   static const char* split_env = getenv("BS_ATTN_SPLIT");
-  int n_split = split_env ? atoi(split_env) : (1024 + B * s.Hkv - 1) / (B * s.Hkv);
+  int n_split = split_env ? atoi(split_env) : (256 + B * s.Hkv / 2) / (B * s.Hkv);   // ~ one workgroup per CU
   n_split = n_split < 1 ? 1 : (n_split > kMaxSplit ? kMaxSplit : n_split);
   const int tiles = (rows_padded(s, k_max)) / 32;
 #define BS_ATTN(NQ, QG)                                                                                         \

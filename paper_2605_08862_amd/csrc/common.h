@@ -25,9 +25,11 @@ constexpr int kTile = 32;               // tokens per MFMA tile inside a page (b
 //
 // float32 pages are row-major [head][token][d] for both K and V.
 //
-// bfloat16 pages are stored in the operand order of the 32x32x16 bf16 MFMA so that the attention
-// kernel's wave-wide 16-byte-per-lane loads are 1 KiB contiguous and feed the matrix unit with no
-// LDS staging and no shuffles.  Per head a page is two tiles of 32 tokens.
+// Pages of bf16 models hold bf16-rounded values (the cache dtype) ENCODED as IEEE float16 (same 16
+// bits per element; exact for 6.1e-5 <= |x| <= 65504), so that they are operands of the f16 MFMA
+// with no conversion in the attention loop.  They are stored in the operand order of the 32x32x16
+// MFMA so that the attention kernel's wave-wide 16-byte-per-lane loads are 1 KiB contiguous and
+// feed the matrix unit with no LDS staging and no shuffles.  Per head a page is two tiles of 32 tokens.
 //   K tile: S^T = K Q^T uses K as the A operand.  A-row m of the tile holds token
 //           tau = 16*(m%8/4) + 4*(m/8) + m%4  (so that accumulator register i of lane group g
 //           is token 16g+i), and lane (m, g) needs, at K-step s, d = g*D/2 + 8s + j (j = 0..7;
@@ -56,7 +58,9 @@ __host__ __device__ __forceinline__ int v_index_bf16(int D, int h, int tok, int 
 template <typename T> __host__ __device__ __forceinline__ int k_index(int D, int h, int tok, int d);
 template <> __host__ __device__ __forceinline__ int k_index<float>(int D, int h, int tok, int d) { return k_index_f32(D, h, tok, d); }
 template <> __host__ __device__ __forceinline__ int k_index<bf16>(int D, int h, int tok, int d) { return k_index_bf16(D, h, tok, d); }
+template <> __host__ __device__ __forceinline__ int k_index<f16>(int D, int h, int tok, int d) { return k_index_bf16(D, h, tok, d); }
 template <typename T> __host__ __device__ __forceinline__ int v_index(int D, int h, int tok, int d);
+template <> __host__ __device__ __forceinline__ int v_index<f16>(int D, int h, int tok, int d) { return v_index_bf16(D, h, tok, d); }
 template <> __host__ __device__ __forceinline__ int v_index<float>(int D, int h, int tok, int d) { return v_index_f32(D, h, tok, d); }
 template <> __host__ __device__ __forceinline__ int v_index<bf16>(int D, int h, int tok, int d) { return v_index_bf16(D, h, tok, d); }
 

@@ -44,10 +44,10 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
 // exactly once, after the rotation): q goes to the query buffer (float16 for bf16 models: it is an
 // attention operand, not cache data), k and v to the slot's page in the cache dtype.  Angles are formed in float64: at positions
 // of 3e4 a float32 angle is already off by ~2e-3 rad.
-template <typename T, typename TQ>
+template <typename T, typename TQ, typename TP>
 __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D, float theta,
                                                           const float* __restrict__ qkv, TQ* __restrict__ q_out,
-                                                          T* __restrict__ k_pages, T* __restrict__ v_pages) {
+                                                          TP* __restrict__ k_pages, TP* __restrict__ v_pages) {
   __shared__ float s_cos[64], s_sin[64];
   int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
@@ -79,20 +79,21 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
       qrow[hh * D + j + half] = from_f32<TQ>(y2);
     } else {
       int kh = hh - Hq;
-      k_pages[pbase + k_index<T>(D, kh, tok, j)] = from_f32<T>(y1);
-      k_pages[pbase + k_index<T>(D, kh, tok, j + half)] = from_f32<T>(y2);
+      // rounded to the cache dtype T, stored in the page encoding TP
+      k_pages[pbase + k_index<TP>(D, kh, tok, j)] = from_f32<TP>(to_f32<T>(from_f32<T>(y1)));
+      k_pages[pbase + k_index<TP>(D, kh, tok, j + half)] = from_f32<TP>(to_f32<T>(from_f32<T>(y2)));
     }
   }
   const float* vrow = row + (size_t)(Hq + Hkv) * D;
   for (int idx = threadIdx.x; idx < Hkv * D; idx += blockDim.x) {
     int kh = idx / D, dd = idx % D;
-    v_pages[pbase + v_index<T>(D, kh, tok, dd)] = from_f32<T>(vrow[idx]);
+    v_pages[pbase + v_index<TP>(D, kh, tok, dd)] = from_f32<TP>(to_f32<T>(from_f32<T>(vrow[idx])));
   }
 }
 
-template <typename T>
-__global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D, int slot, int pos0, T* __restrict__ k_pages,
-                                                      T* __restrict__ v_pages, T* __restrict__ k_rows,
+template <typename T, typename TP>
+__global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D, int slot, int pos0, TP* __restrict__ k_pages,
+                                                      TP* __restrict__ v_pages, T* __restrict__ k_rows,
                                                       T* __restrict__ v_rows, int to_pages) {
   int i = blockIdx.x, pos = pos0 + i;
   int page = kv.block_table[(size_t)slot * kv.max_pages + pos / kPage];
@@ -101,10 +102,15 @@ __global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D,
   size_t pbase = (size_t)page * kv_page_elems(Hkv, D);
   for (int idx = threadIdx.x; idx < Hkv * D; idx += blockDim.x) {
     int kh = idx / D, dd = idx % D;
-    size_t ki = pbase + k_index<T>(D, kh, tok, dd), vi = pbase + v_index<T>(D, kh, tok, dd);
+    size_t ki = pbase + k_index<TP>(D, kh, tok, dd), vi = pbase + v_index<TP>(D, kh, tok, dd);
     size_t ri = (size_t)i * Hkv * D + idx;
-    if (to_pages) { k_pages[ki] = k_rows[ri]; v_pages[vi] = v_rows[ri]; }
-    else { k_rows[ri] = k_pages[ki]; v_rows[ri] = v_pages[vi]; }
+    if (to_pages) {
+      k_pages[ki] = from_f32<TP>(to_f32<T>(k_rows[ri]));
+      v_pages[vi] = from_f32<TP>(to_f32<T>(v_rows[ri]));
+    } else {
+      k_rows[ri] = from_f32<T>(to_f32<TP>(k_pages[ki]));
+      v_rows[ri] = from_f32<T>(to_f32<TP>(v_pages[vi]));
+    }
   }
 }
 
@@ -119,19 +125,19 @@ void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, co
 void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, void* q_out,
                         void* k_pages, void* v_pages, hipStream_t st) {
   if (s.dtype == BS_F32)
-    hipLaunchKernelGGL((rope_append_kernel<float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+    hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
                        qkv, (float*)q_out, (float*)k_pages, (float*)v_pages);
   else
-    hipLaunchKernelGGL((rope_append_kernel<bf16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
-                       qkv, (f16*)q_out, (bf16*)k_pages, (bf16*)v_pages);
+    hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+                       qkv, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st) {
   if (n <= 0) return;
   if (s.dtype == BS_F32)
-    hipLaunchKernelGGL(kv_copy_kernel<float>, dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (float*)k_pages,
+    hipLaunchKernelGGL((kv_copy_kernel<float, float>), dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (float*)k_pages,
                        (float*)v_pages, (float*)k_rows, (float*)v_rows, to_pages ? 1 : 0);
   else
-    hipLaunchKernelGGL(kv_copy_kernel<bf16>, dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (bf16*)k_pages,
-                       (bf16*)v_pages, (bf16*)k_rows, (bf16*)v_rows, to_pages ? 1 : 0);
+    hipLaunchKernelGGL((kv_copy_kernel<bf16, f16>), dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (f16*)k_pages,
+                       (f16*)v_pages, (bf16*)k_rows, (bf16*)v_rows, to_pages ? 1 : 0);
 }

@@ -34,7 +34,8 @@ class Engine:
         self.cdesc = B.make_desc(desc)
         self.B_max, self.k_max = B_max, k_max
         self.weights = weights
-        td = TORCH_DTYPE[desc["dtype"]]
+        # page encoding: float32 models store float32; bf16 models store bf16-rounded values as float16 bits
+        td = torch.float32 if desc["dtype"] == B.BS_F32 else torch.float16
         P = B.BS_PAGE_TOKENS
         self.max_pages = (max_ctx + P - 1) // P
         self.n_slots = n_slots
