@@ -22,6 +22,7 @@ struct bs_ctx {
   void* a;             // normed rows      [M_max, d] (GEMM operand type: float32 / float16)
   float* qkv;          // [M_max, (Hq+2Hkv) D] float32 projection (rounded once, after the rotation)
   void* q;             // [M_max, Hq D] rotated queries
+  float* slabs;        // bf16 models: K-split slabs of the float32 GEMM epilogues [8][M_max, max(Nqkv, d)]
   void* attn_out;      // [M_max, Hq D]
   void* act;           // [M_max, F]
   void* hf;            // final-norm rows  [M_max, d]
@@ -95,6 +96,9 @@ size_t carve(bs_ctx* c, char* base) {
   c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
   c->qkv = w.take<float>((size_t)M * s.Nqkv());
   c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
+  c->slabs = (s.dtype == BS_BF16)
+                 ? w.take<float>((size_t)kMaxGemmSplit * M * (s.Nqkv() > s.d ? s.Nqkv() : s.d))
+                 : nullptr;
   c->attn_out = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
   c->act = w.take<char>((size_t)M * s.F * elt(s.dtype));
   c->hf = w.take<char>((size_t)M * s.d * elt(s.dtype));
@@ -325,22 +329,29 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   const Plan& p = c->plan;
   launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, st);
   launch_embed(s, p, M_max, c->embed, c->h, st);
+  const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
+  int pending = 0;                              // slabs of the last residual projection not yet added to h
   for (int l = 0; l < s.L; ++l) {
-    launch_rmsnorm(s, p, M_max, c->h, c->attn_norm[l], c->a, st);
+    launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->attn_norm[l], c->a, st);
+    int nq;
     { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
-      launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l], c->qkv, st); }
-    launch_rope_append(s, p, c->kv, M_max, c->qkv, c->q, c->k_pages[l], c->v_pages[l], st);
+      nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
+                       slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
+    launch_rope_append(s, p, c->kv, M_max, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
+                       c->v_pages[l], st);
     launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
     { ProfScope ps(c, BS_PROF_GEMM_O, st);
-      launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l], c->h, st); }
-    launch_rmsnorm(s, p, M_max, c->h, c->mlp_norm[l], c->a, st);
+      pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l],
+                            slab_mode ? (void*)c->slabs : (void*)c->h, st); }
+    launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->mlp_norm[l], c->a, st);
     { ProfScope ps(c, BS_PROF_GEMM_GATE_UP, st);
       launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st); }
     { ProfScope ps(c, BS_PROF_GEMM_DOWN, st);
-      launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l], c->h, st); }
+      pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l],
+                            slab_mode ? (void*)c->slabs : (void*)c->h, st); }
   }
-  launch_rmsnorm(s, p, M_max, c->h, c->final_norm, c->hf, st);
+  launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->final_norm, c->hf, st);
   if (logits_debug && s.dtype == BS_F32)
     launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, logits_debug, st);
   if (logits_debug && s.dtype == BS_BF16) {

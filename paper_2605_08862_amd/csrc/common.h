@@ -103,18 +103,24 @@ void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_sl
 void launch_clear_status(int32_t* status, hipStream_t st);
 // elementwise.hip
 void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, hipStream_t st);
-void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, const float* gain, void* out,
-                    hipStream_t st);
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, void* q_out,
-                        void* k_pages, void* v_pages, hipStream_t st);
+// h[r] += sum of n_slabs slabs [M_max, d] (n_slabs may be 0), then out[r] = RMSNorm(h[r]).
+void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
+                    const float* gain, void* out, hipStream_t st);
+// qkv is the float32 projection, given as n_slabs >= 1 slabs [M_max, Nqkv] that are summed.
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, int n_slabs,
+                        void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
 // gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue.  float32 models: A, W float32 row-major.
 // bf16 models: A float16 row-major, W the packed float16 copy made by launch_pack_weight.
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3 };
-void launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
-                 const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
-                 hipStream_t st);
+// Returns the number of K-split slabs written (bf16 models, EPI_RESID_ADD / EPI_STORE_F32: `out` is the
+// slab buffer [split][M_max][N] and the consumer sums the slabs), or 0 when `out` was updated in place
+// (float32 models).
+constexpr int kMaxGemmSplit = 8;
+int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
+                const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
+                hipStream_t st);
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st);
 // attention.hip

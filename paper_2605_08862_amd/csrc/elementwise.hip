@@ -24,15 +24,28 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 
 // out[r] = h[r] * gain / sqrt(mean(h[r]^2) + eps), float32 in; out is the GEMM operand type
 // (float32 for float32 models, float16 for bf16 models).
+// With n_slabs > 0 the row first absorbs the K-split slabs of the preceding residual projection:
+// h[r] += sum_s slabs[s][r] (the updated residual is written back).
 template <typename T>
-__global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, const float* __restrict__ h,
+__global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, float* __restrict__ h,
+                                                      const float* __restrict__ slabs, int n_slabs, size_t slab_stride,
                                                       const float* __restrict__ gain, T* __restrict__ out) {
   __shared__ float red[4];
   int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
-  const float* x = h + (size_t)r * d;
+  float* x = h + (size_t)r * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) { float v = x[i]; ss += v * v; }
+  if (n_slabs > 0) {
+    const float* sl = slabs + (size_t)r * d;
+    for (int i = threadIdx.x; i < d; i += 256) {
+      float v = x[i];
+      for (int s = 0; s < n_slabs; ++s) v += sl[(size_t)s * slab_stride + i];
+      x[i] = v;
+      ss += v * v;
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += 256) { float v = x[i]; ss += v * v; }
+  }
   ss = block_sum_256(ss, red);
   float inv = 1.0f / sqrtf(ss / (float)d + eps);
   T* o = out + (size_t)r * d;
@@ -46,8 +59,9 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
 // of 3e4 a float32 angle is already off by ~2e-3 rad.
 template <typename T, typename TQ, typename TP>
 __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D, float theta,
-                                                          const float* __restrict__ qkv, TQ* __restrict__ q_out,
-                                                          TP* __restrict__ k_pages, TP* __restrict__ v_pages) {
+                                                          const float* __restrict__ qkv, int n_slabs, size_t slab_stride,
+                                                          TQ* __restrict__ q_out, TP* __restrict__ k_pages,
+                                                          TP* __restrict__ v_pages) {
   __shared__ float s_cos[64], s_sin[64];
   int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
@@ -72,6 +86,7 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
     int hh = idx / half, j = idx % half;
     const float* x = row + (size_t)hh * D;
     float x1 = x[j], x2 = x[j + half];
+    for (int sl = 1; sl < n_slabs; ++sl) { x1 += x[sl * slab_stride + j]; x2 += x[sl * slab_stride + j + half]; }
     float c = s_cos[j], s = s_sin[j];
     float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
     if (hh < Hq) {
@@ -87,7 +102,9 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
   const float* vrow = row + (size_t)(Hq + Hkv) * D;
   for (int idx = threadIdx.x; idx < Hkv * D; idx += blockDim.x) {
     int kh = idx / D, dd = idx % D;
-    v_pages[pbase + v_index<TP>(D, kh, tok, dd)] = from_f32<TP>(to_f32<T>(from_f32<T>(vrow[idx])));
+    float v = vrow[idx];
+    for (int sl = 1; sl < n_slabs; ++sl) v += vrow[sl * slab_stride + idx];
+    v_pages[pbase + v_index<TP>(D, kh, tok, dd)] = from_f32<TP>(to_f32<T>(from_f32<T>(v)));
   }
 }
 
@@ -118,18 +135,23 @@ void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, f
   if (s.dtype == BS_F32) hipLaunchKernelGGL(embed_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, (const float*)embed, h);
   else hipLaunchKernelGGL(embed_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, s.d, (const bf16*)embed, h);
 }
-void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, const float* h, const float* gain, void* out, hipStream_t st) {
-  if (s.dtype == BS_F32) hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, gain, (float*)out);
-  else hipLaunchKernelGGL(rmsnorm_kernel<f16>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, gain, (f16*)out);
+void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
+                    const float* gain, void* out, hipStream_t st) {
+  const size_t stride = (size_t)M_max * s.d;
+  if (s.dtype == BS_F32)
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (float*)out);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<f16>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (f16*)out);
 }
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, void* q_out,
-                        void* k_pages, void* v_pages, hipStream_t st) {
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, int n_slabs,
+                        void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
+  const size_t stride = (size_t)M_max * s.Nqkv();
   if (s.dtype == BS_F32)
     hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
-                       qkv, (float*)q_out, (float*)k_pages, (float*)v_pages);
+                       qkv, n_slabs, stride, (float*)q_out, (float*)k_pages, (float*)v_pages);
   else
     hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
-                       qkv, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
+                       qkv, n_slabs, stride, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st) {

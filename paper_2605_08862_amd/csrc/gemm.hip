@@ -6,6 +6,9 @@
 #include <stdlib.h>
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+// same function with the hardware reciprocal (1 ulp): used in the MFMA epilogue, where a full-precision
+// division per output element costs more than the matrix products of a small tile
+__device__ __forceinline__ float silu_fast(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 // ------------------------------------------------------------------ plain FMA kernel (float32 models)
 // 64x64 output tile, K step 16, 256 threads, 4x4 outputs per thread.  For EPI_SWIGLU the tile
@@ -108,13 +111,17 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 // tiles of a wave are the gate rows and the matching up rows of the same 32 output features, so both
 // land in the same lane.  Grid: x = (M block, N block) pairs, remapped so that the M blocks sharing
 // a weight tile run back to back on one XCD (ids are dealt round-robin to the 8 XCDs) and hit its
-// L2; y = K split (EPI_RESID_ADD only: partial sums are added to the float32 residual atomically).
+// L2; y = K split.  The float32 epilogues (QKV projection, residual projections) write one partial
+// [M_max, N] slab per K split, out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums
+// the slabs.  Float atomics into the residual were measured at ~25 us per launch and are not used.
 template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
                                                         int m_blocks, int n_blocks) {
-  using G = MfmaGemm<MT, NT, false>;
+  // accumulators hold C^T tiles (SWAP): a lane owns one activation row and, per group of four
+  // registers, four consecutive output columns, so the epilogue stores 8 or 16 bytes per lane
+  using G = MfmaGemm<MT, NT, true>;
   extern __shared__ __align__(16) char lds[];
   const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
   const int total = m_blocks * n_blocks;
@@ -160,26 +167,39 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
   const int kt0 = (int)((long)nk * blockIdx.y / n_split), kt1 = (int)((long)nk * (blockIdx.y + 1) / n_split);
   G::run(acc, op, kt0, kt1, lds);
 
+  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+  const int ln = lane & 31, lg = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < MT; ++mi) {
+    const int m = m0 + mi * 32 + ln;
+    if (m >= M) continue;
+    if (GLU) {
+      if (n_wave0 >= N) continue;                        // N is a multiple of 32: whole tiles only
+      f16* dst = (f16*)out + (size_t)m * N + n_wave0 + 4 * lg;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int m = m0 + mi * 32 + acc_row(lane, i);
-      if (m >= M) continue;
-      if (GLU) {
-        const int n = n_wave0 + acc_col(lane);
-        if (n < N) ((f16*)out)[(size_t)m * N + n] = (f16)(silu_f(acc[mi][0][i]) * acc[mi][NT - 1][i]);
-      } else {
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f16x4 v;
 #pragma unroll
-        for (int ni = 0; ni < NT; ++ni) {
-          const int n = n_wave0 + ni * 32 + acc_col(lane);
-          if (n >= N) continue;
-          const size_t o = (size_t)m * N + n;
-          if (EPI == EPI_STORE) ((f16*)out)[o] = (f16)acc[mi][ni][i];
-          else if (EPI == EPI_RESID_ADD) {
-            if (n_split == 1) ((float*)out)[o] += acc[mi][ni][i];
-            else atomicAdd((float*)out + o, acc[mi][ni][i]);
-          } else ((float*)out)[o] = acc[mi][ni][i];
+        for (int j = 0; j < 4; ++j) v[j] = (f16)(silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][NT - 1][4 * i4 + j]);
+        *(f16x4*)(dst + 8 * i4) = v;
+      }
+    } else {
+#pragma unroll
+      for (int ni = 0; ni < NT; ++ni) {
+        const int n0 = n_wave0 + ni * 32;
+        if (n0 >= N) continue;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const size_t o = (size_t)m * N + n0 + 8 * i4 + 4 * lg;
+          if (EPI == EPI_STORE) {
+            f16x4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (f16)acc[mi][ni][4 * i4 + j];
+            *(f16x4*)((f16*)out + o) = v;
+          } else {
+            *(f32x4*)((float*)out + (size_t)blockIdx.y * M_max * N + o) =
+                f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
+          }
         }
       }
     }
@@ -189,7 +209,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
 template <int MT, int NT, int EPI>
 static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
                         const void* W, void* out, int n_split, hipStream_t st) {
-  using G = MfmaGemm<MT, NT, false>;
+  using G = MfmaGemm<MT, NT, true>;
   constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * 32 : 4 * NT * 32;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
   int total = m_blocks * n_blocks;
@@ -218,9 +238,9 @@ static int pick_mt(int M_max) {
 }
 
 template <int EPI>
-static void dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
-                     const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
-  if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return; }
+static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
+                    const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
+  if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return 0; }
   static const char* env_split = getenv("BS_GEMM_SPLIT");          // tuning aids
   static const char* env_nt = getenv("BS_GEMM_NT");
   const int mt = pick_mt(M_max);
@@ -234,31 +254,33 @@ static void dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int
   const int nout = (EPI == EPI_SWIGLU) ? 128 : nt * 128;
   const int blocks = m_blocks * ((N + nout - 1) / nout);
   int n_split = 1;
-  if (EPI == EPI_RESID_ADD) {
+  if (EPI == EPI_RESID_ADD || EPI == EPI_STORE_F32) {
     const int nk = K / kBK;
-    if (blocks < 160) n_split = (256 + blocks - 1) / blocks;
+    if (blocks < 160) n_split = (256 + blocks / 2) / blocks;
     if (n_split > nk / 4) n_split = nk / 4 > 0 ? nk / 4 : 1;       // at least 4 K tiles per split
     if (env_split) n_split = atoi(env_split);
     if (n_split < 1) n_split = 1;
+    if (n_split > kMaxGemmSplit) n_split = kMaxGemmSplit;
     if (n_split > nk) n_split = nk;
   }
 #define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
   if constexpr (EPI != EPI_SWIGLU) {
     if (nt == 1) {
       switch (mt) { case 1: BS_GEMM(1, 1); break; case 2: BS_GEMM(2, 1); break; case 4: BS_GEMM(4, 1); break; default: BS_GEMM(6, 1); }
-      return;
+      return n_split;
     }
   }
   switch (mt) { case 1: BS_GEMM(1, 2); break; case 2: BS_GEMM(2, 2); break; case 4: BS_GEMM(4, 2); break; default: BS_GEMM(6, 2); }
 #undef BS_GEMM
+  return n_split;
 }
 
-void launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
-                 const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
+int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
+                const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
   switch (epi) {
-    case EPI_STORE: dispatch<EPI_STORE>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st); break;
-    case EPI_RESID_ADD: dispatch<EPI_RESID_ADD>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st); break;
-    case EPI_SWIGLU: dispatch<EPI_SWIGLU>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st); break;
-    case EPI_STORE_F32: dispatch<EPI_STORE_F32>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st); break;
+    case EPI_STORE: return dispatch<EPI_STORE>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+    case EPI_RESID_ADD: return dispatch<EPI_RESID_ADD>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+    case EPI_SWIGLU: return dispatch<EPI_SWIGLU>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+    default: return dispatch<EPI_STORE_F32>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
   }
 }

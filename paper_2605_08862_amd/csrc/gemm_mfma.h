@@ -56,18 +56,24 @@ struct MfmaGemm {
   static constexpr int LDS_STAGE_BYTES = MT * 4 * 1024;        // MT row tiles x 4 K-steps x 1 KiB
   static constexpr int LDS_BYTES = 2 * LDS_STAGE_BYTES;
 
-  // Chunk assignment of thread t for the activation tile: chunk q = i*256 + t covers
-  // (row, g, s) with g = q / (BM*4), row = (q % (BM*4)) / 4, s = q % 4: a wave touches 16 rows x
-  // 64 contiguous bytes in global memory and 16 distinct bank groups in LDS.
+  // Chunk assignment of thread t for the activation tile: chunk q = i*256 + t is the q%8-th 16-byte
+  // piece of row q/8, i.e. (g, s) = (q%8 / 4, q%4): eight consecutive lanes read one full 128-byte line
+  // of a row.  In LDS the 16-byte slot of (row, g, s) inside its 1 KiB fragment is XOR-swizzled with
+  // s + 4g, so that those eight lanes hit eight different bank groups (measured: the unswizzled layout
+  // spent 576 LDS conflict cycles per K tile); the fragment reader applies the same permutation and
+  // still sweeps its fragment as 64 distinct slots.
   __device__ static __forceinline__ void chunk_of(int i, int& row, int& g, int& s) {
     int q = i * 256 + threadIdx.x;
-    g = q / (BM * 4);
-    int rem = q % (BM * 4);
-    row = rem >> 2;
-    s = rem & 3;
+    row = q >> 3;
+    g = (q >> 2) & 1;
+    s = q & 3;
   }
   __device__ static __forceinline__ int chunk_lds_offset(int row, int g, int s) {
-    return (((row >> 5) * 4 + s) * 64 + g * 32 + (row & 31)) * 16;
+    return (((row >> 5) * 4 + s) * 64 + ((g * 32 + (row & 31)) ^ (s + 4 * g))) * 16;
+  }
+  // byte offset of lane `lane`'s slot in fragment (mi, s)
+  __device__ static __forceinline__ int frag_lds_offset(int mi, int s, int lane) {
+    return ((mi * 4 + s) * 64 + (lane ^ (s + 4 * (lane >> 5)))) * 16;
   }
 
   struct Operands {
@@ -81,37 +87,70 @@ struct MfmaGemm {
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
+      for (int s = 0; s < 4; ++s) {
+#ifdef BS_DBG_NOW
+        if (kt > 0) continue;
+#endif
         wreg[STAGE][ni][s] = *(const u32x4*)(op.w_tiles[ni] + (size_t)kt * kWBlock + s * 512);
+      }
   }
 
   template <int STAGE>
-  __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[MT],
+  __device__ static __forceinline__ void load_x(u32x4 (&xreg)[3][MT], const Operands& op, int kt) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#ifdef BS_DBG_NOX
+      if (kt > 0) continue;
+#endif
+      xreg[STAGE][i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt * kBK);
+    }
+  }
+
+  // One K tile.  STAGE = (kt - kt0) % 3 names the register ring slots: weights of tile j live in
+  // wreg[j % 3], activation chunks of tile j in xreg[j % 3] until they are written to LDS stage j & 1.
+  // Both streams are requested two iterations before they are needed: measured on MI355X, a one-
+  // iteration distance for the activations (L2 / fabric latency ~1-2 us) left the waves waiting on
+  // vmcnt for ~40 % of their lifetime.
+  template <int STAGE>
+  __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[3][MT],
                                               const Operands& op, int kt, int kt1, char* lds) {
     const int lane = threadIdx.x & 63;
     if (kt + 1 < kt1) {                                   // activations of the next K tile -> LDS
       char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) *(u32x4*)(nstage + op.x_lds[i]) = xreg[i];
+      for (int i = 0; i < MT; ++i) *(u32x4*)(nstage + op.x_lds[i]) = xreg[(STAGE + 1) % 3][i];
     }
-    if (kt + 2 < kt1) {                                   // global loads two K tiles ahead
-#pragma unroll
-      for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)(kt + 2) * kBK);
-      load_w<(STAGE + 2) % 3>(wreg, op, kt + 2);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 3 < kt1) load_x<STAGE>(xreg, op, kt + 3);    // slot of tile kt is free (written to LDS last iteration)
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 2 < kt1) load_w<(STAGE + 2) % 3>(wreg, op, kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    // fragment reads run one K-step ahead of the MFMAs that consume them (LDS latency hidden)
     const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
+    u32x4 xf[2][MT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) xf[0][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, 0, lane));
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
+      if (s < 3) {
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int mi = 0; mi < MT; ++mi) {
-        const f16x8 xf = as_f16x8(*(const u32x4*)(stage + ((mi * 4 + s) * 64 + lane) * 16));
+        const f16x8 x = as_f16x8(xf[s & 1][mi]);
 #pragma unroll
         for (int ni = 0; ni < NT; ++ni) {
           const f16x8 wf = as_f16x8(wreg[STAGE][ni][s]);
-          if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, xf, acc[mi][ni], 0, 0, 0);
-          else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf, acc[mi][ni], 0, 0, 0);
+#ifdef BS_DBG_NOMFMA
+          if (mi + ni + s > 0) continue;
+#endif
+          if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, x, acc[mi][ni], 0, 0, 0);
+          else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, wf, acc[mi][ni], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
   }
@@ -119,19 +158,16 @@ struct MfmaGemm {
   // Accumulates K tiles [kt0, kt1) into acc.  All 256 threads of the workgroup must call it.
   __device__ static __forceinline__ void run(f32x16 (&acc)[MT][NT], const Operands& op, int kt0, int kt1, char* lds) {
     if (kt0 >= kt1) return;
-    u32x4 xreg[MT];
+    u32x4 xreg[3][MT];
     u32x4 wreg[3][NT][4];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt0 * kBK);
+    // ring slots are indexed relative to kt0, LDS stages by the absolute tile parity
+    load_x<0>(xreg, op, kt0);
     load_w<0>(wreg, op, kt0);
-    if (kt0 + 1 < kt1) load_w<1>(wreg, op, kt0 + 1);
+    if (kt0 + 1 < kt1) { load_x<1>(xreg, op, kt0 + 1); load_w<1>(wreg, op, kt0 + 1); }
+    if (kt0 + 2 < kt1) load_x<2>(xreg, op, kt0 + 2);
     char* stage0 = lds + (kt0 & 1) * LDS_STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[i];
-    if (kt0 + 1 < kt1) {
-#pragma unroll
-      for (int i = 0; i < MT; ++i) xreg[i] = *(const u32x4*)(op.x_rows[i] + (size_t)(kt0 + 1) * kBK);
-    }
+    for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[0][i];
     __syncthreads();
     for (int kt = kt0; kt < kt1; kt += 3) {
       body<0>(acc, wreg, xreg, op, kt, kt1, lds);
