@@ -109,8 +109,16 @@ size_t carve(bs_ctx* c, char* base) {
   sb.part_sum = w.take<float>((size_t)c->n_vtiles * M);
   sb.part_arg = w.take<int32_t>((size_t)c->n_vtiles * M);
   sb.z_target = w.take<float>(M);
+  sb.row_max = w.take<float>(M);
+  sb.row_lse = w.take<float>(M);
+  sb.row_arg = w.take<int32_t>(M);
+  sb.q_max = w.take<float>(M);
   sb.q_lse = w.take<float>(M);
   sb.q_target = w.take<float>(M);
+  sb.sel_pmax = w.take<float>(B);
+  sb.sel_qmax = w.take<float>(B);
+  sb.samp_sum = w.take<double>((size_t)B * 32 * 2);
+  sb.samp_mass = w.take<double>((size_t)B * 32 * 2);
   sb.sel_row = w.take<int32_t>(B);
   sb.sel_mode = w.take<int32_t>(B);
   sb.sel_qrow = w.take<int32_t>(B);

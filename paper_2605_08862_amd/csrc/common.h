@@ -133,8 +133,11 @@ size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
 struct SamplerBufs {
   float* part_max; float* part_sum; int32_t* part_arg;   // [n_vtiles, M_max]
   float* z_target;                                       // [M_max] logit of the judged draft token
-  float* q_lse; float* q_target;                         // [M_max] per query row that judges a draft
+  float* row_max; float* row_lse; int32_t* row_arg;      // [M_max] combined statistics of each packed row
+  float* q_max; float* q_lse; float* q_target;           // [M_max] per query row that judges a draft
   int32_t* sel_row; int32_t* sel_mode; int32_t* sel_qrow; int32_t* sel_tok; // [B_max]
+  float* sel_pmax; float* sel_qmax;                      // [B_max] raw maxima of the sampled row / its q row
+  double* samp_sum; double* samp_mass;                   // [B_max, 32 chunks, 2] sampling partials
   float* sel_logits;                                     // [B_max, V]
 };
 int lmhead_vtiles(int V);

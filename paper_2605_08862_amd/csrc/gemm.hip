@@ -131,6 +131,9 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
   const int mb = id % m_blocks, nb = id / m_blocks;
   const int m0 = mb * G::BM;
   if (m0 >= M) return;
+#ifdef BS_DBG_EXIT0
+  return;
+#endif
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   static_assert(!GLU || NT == 2, "SwiGLU pairs one gate tile with one up tile per wave");
   constexpr int NOUT_W = GLU ? 32 : NT * 32;            // output columns per wave
@@ -167,6 +170,9 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restric
   const int kt0 = (int)((long)nk * blockIdx.y / n_split), kt1 = (int)((long)nk * (blockIdx.y + 1) / n_split);
   G::run(acc, op, kt0, kt1, lds);
 
+#ifdef BS_DBG_NOEPI
+  if (acc[0][0][0] != 12345.678f) return;
+#endif
   typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
 #pragma unroll

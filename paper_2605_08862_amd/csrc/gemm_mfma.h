@@ -115,15 +115,23 @@ struct MfmaGemm {
   __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[3][MT],
                                               const Operands& op, int kt, int kt1, char* lds) {
     const int lane = threadIdx.x & 63;
-    if (kt + 1 < kt1) {                                   // activations of the next K tile -> LDS
+    // Every load and store below is UNCONDITIONAL (tile indices are clamped to the last tile instead):
+    // a prefetch issued under a condition makes the compiler's wait-count tracking assume it may be
+    // the newest outstanding load, and the resulting vmcnt(0) waits serialise the whole ring.
+    {                                                     // activations of the next K tile -> LDS
       char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) *(u32x4*)(nstage + op.x_lds[i]) = xreg[(STAGE + 1) % 3][i];
+      for (int i = 0; i < MT; ++i) {
+#ifdef BS_DBG_NOLDS
+        if (kt > 0) continue;
+#endif
+        *(u32x4*)(nstage + op.x_lds[i]) = xreg[(STAGE + 1) % 3][i];
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 3 < kt1) load_x<STAGE>(xreg, op, kt + 3);    // slot of tile kt is free (written to LDS last iteration)
+    load_x<STAGE>(xreg, op, min(kt + 3, kt1 - 1));        // slot of tile kt is free (written to LDS last iteration)
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 2 < kt1) load_w<(STAGE + 2) % 3>(wreg, op, kt + 2);
+    load_w<(STAGE + 2) % 3>(wreg, op, min(kt + 2, kt1 - 1));
     __builtin_amdgcn_sched_barrier(0);
     // fragment reads run one K-step ahead of the MFMAs that consume them (LDS latency hidden)
     const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
@@ -134,7 +142,13 @@ struct MfmaGemm {
     for (int s = 0; s < 4; ++s) {
       if (s < 3) {
 #pragma unroll
-        for (int mi = 0; mi < MT; ++mi) xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
+        for (int mi = 0; mi < MT; ++mi) {
+#ifdef BS_DBG_NOLDS
+          xf[(s + 1) & 1][mi] = xf[s & 1][mi];
+#else
+          xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
+#endif
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -163,8 +177,9 @@ struct MfmaGemm {
     // ring slots are indexed relative to kt0, LDS stages by the absolute tile parity
     load_x<0>(xreg, op, kt0);
     load_w<0>(wreg, op, kt0);
-    if (kt0 + 1 < kt1) { load_x<1>(xreg, op, kt0 + 1); load_w<1>(wreg, op, kt0 + 1); }
-    if (kt0 + 2 < kt1) load_x<2>(xreg, op, kt0 + 2);
+    load_x<1>(xreg, op, min(kt0 + 1, kt1 - 1));
+    load_w<1>(wreg, op, min(kt0 + 1, kt1 - 1));
+    load_x<2>(xreg, op, min(kt0 + 2, kt1 - 1));
     char* stage0 = lds + (kt0 & 1) * LDS_STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[0][i];

@@ -10,8 +10,9 @@
 
 enum { MODE_NONE = 0, MODE_PLAIN = 1, MODE_RESID_ONEHOT = 2, MODE_RESID_DENSE = 3 };
 
-constexpr int kLmMT = 4, kLmNT = 2;                 // LM-head wave tile: 128 rows x 64 vocab entries
+constexpr int kLmNT = 2;                            // LM-head wave tile: 32*MT rows x 64 vocab entries
 constexpr int kLmVtile = kLmNT * 32;                // vocab entries per statistics tile (bf16 path)
+constexpr int kSampleChunks = 32;                   // vocabulary chunks per sequence in the sampling kernels
 constexpr int kRowVtile = 1024;                     // vocab entries per statistics tile (logits path)
 
 int lmhead_vtiles(int V) {
@@ -23,7 +24,7 @@ int lmhead_vtiles(int V) {
 // STATS = true : rows are the packed query rows; epilogue writes statistics (+ optional debug logits).
 // STATS = false: rows are gathered through sel_row (one per sequence); epilogue stores float32 logits
 //                to sel_logits [B, V].
-template <bool STATS>
+template <int kLmMT, bool STATS>
 __global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int V, int K,
                                                      const f16* __restrict__ X, const int32_t* __restrict__ x_rows,
                                                      const f16* __restrict__ W, float inv_temp,
@@ -166,103 +167,128 @@ __global__ void __launch_bounds__(256) logit_stats_kernel(Plan p, int M_max, int
   }
 }
 
+// ------------------------------------------------------------------ per-row statistics
+// Combines the per-tile (max, sum exp, arg max) of one packed row: row_max (raw logit), row_lse of z/T,
+// row_arg (first arg max).  One workgroup per row; tile entries of a row are M_max apart.
+__global__ void __launch_bounds__(256) row_stats_kernel(Plan p, int M_max, int n_vtiles, float inv_temp, SamplerBufs sb) {
+  __shared__ float s_mx[4], s_sum[4];
+  __shared__ int s_arg[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  if (r >= p.n_rows[0]) return;
+  float mx = -INFINITY;
+  int arg = 0x7fffffff;
+  for (int vt = tid; vt < n_vtiles; vt += 256) {
+    const float m2 = sb.part_max[(size_t)vt * M_max + r];
+    const int a2 = sb.part_arg[(size_t)vt * M_max + r];
+    if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float mo = __shfl_xor(mx, o);
+    const int ao = __shfl_xor(arg, o);
+    if (mo > mx || (mo == mx && ao < arg)) { mx = mo; arg = ao; }
+  }
+  if ((tid & 63) == 0) { s_mx[tid >> 6] = mx; s_arg[tid >> 6] = arg; }
+  __syncthreads();
+  mx = s_mx[0]; arg = s_arg[0];
+  for (int w = 1; w < 4; ++w)
+    if (s_mx[w] > mx || (s_mx[w] == mx && s_arg[w] < arg)) { mx = s_mx[w]; arg = s_arg[w]; }
+  float sum = 0.f;
+  for (int vt = tid; vt < n_vtiles; vt += 256) {
+    const float m2 = sb.part_max[(size_t)vt * M_max + r];
+    if (m2 > -INFINITY) sum += sb.part_sum[(size_t)vt * M_max + r] * __expf((m2 - mx) * inv_temp);
+  }
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    sb.row_max[r] = mx;
+    sb.row_lse[r] = mx * inv_temp + logf(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
+    sb.row_arg[r] = arg;
+  }
+}
+
 // ------------------------------------------------------------------ proposal statistics
-// For every query row that judges a draft: log-sum-exp of its q_logits row and q_logits[draft].
+// For every query row that judges a draft: max and log-sum-exp of its q_logits row and q_logits[draft].
+// One pass (online max / rescaled sum), 16-byte loads.
+template <typename Q> struct QVec;
+template <> struct QVec<float> { static constexpr int N = 4; };
+template <> struct QVec<bf16> { static constexpr int N = 8; };
+
 template <typename Q>
 __global__ void __launch_bounds__(256) q_stats_kernel(Plan p, int V, const Q* __restrict__ q_logits, SamplerBufs sb) {
-  __shared__ float s_red[4];
-  const int r = blockIdx.x;
+  __shared__ float s_m[4], s_s[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
   if (r >= p.n_rows[0]) return;
   const int tgt = p.row_target[r];
   if (tgt < 0) return;
   const int b = p.row_seq[r];
   const Q* q = q_logits + (size_t)(p.draft_start[b] + p.row_pos[r]) * V;
-  float mx = -INFINITY;
-  for (int n = threadIdx.x; n < V; n += 256) mx = fmaxf(mx, to_f32<Q>(q[n]));
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
+  constexpr int N = QVec<Q>::N;
+  float m = -INFINITY, sum = 0.f;
+  auto absorb = [&](float x) {
+    if (x > m) { sum = sum * __expf(m - x) + 1.0f; m = x; }   // exp(-inf) = 0 on the first element
+    else sum += __expf(x - m);
+  };
+  const bool aligned = (((uintptr_t)q) & 15) == 0;
+  const int nvec = aligned ? V / N : 0;
+  for (int i = tid; i < nvec; i += 256) {
+    const u32x4 raw = *(const u32x4*)(q + (size_t)i * N);
+    if (N == 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) absorb(__uint_as_float(raw[j]));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { absorb(__uint_as_float(raw[j] << 16)); absorb(__uint_as_float(raw[j] & 0xffff0000u)); }
+    }
+  }
+  for (int n = nvec * N + tid; n < V; n += 256) absorb(to_f32<Q>(q[n]));
+  for (int o = 32; o > 0; o >>= 1) {
+    const float mo = __shfl_xor(m, o), so = __shfl_xor(sum, o);
+    const float mn = fmaxf(m, mo);
+    sum = (m == -INFINITY ? 0.f : sum * __expf(m - mn)) + (mo == -INFINITY ? 0.f : so * __expf(mo - mn));
+    m = mn;
+  }
+  if ((tid & 63) == 0) { s_m[tid >> 6] = m; s_s[tid >> 6] = sum; }
   __syncthreads();
-  mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-  __syncthreads();
-  float sum = 0.f;
-  for (int n = threadIdx.x; n < V; n += 256) sum += __expf(to_f32<Q>(q[n]) - mx);
-  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    sb.q_lse[r] = mx + logf(s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+  if (tid == 0) {
+    float mt = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3])), st = 0.f;
+    for (int w = 0; w < 4; ++w) if (s_m[w] > -INFINITY) st += s_s[w] * __expf(s_m[w] - mt);
+    sb.q_max[r] = mt;
+    sb.q_lse[r] = mt + logf(st);
     sb.q_target[r] = to_f32<Q>(q[tgt]);
   }
 }
 
 // ------------------------------------------------------------------ accept scan (Alg. 1 inner loop, Eq. 2)
-__global__ void __launch_bounds__(256) accept_scan_kernel(Plan p, int k_max, int M_max, int n_vtiles, int dense_q,
-                                                          float temperature, int eos_id, int emit_bonus,
-                                                          const float* __restrict__ u_accept, SamplerBufs sb,
-                                                          int32_t* __restrict__ n_accepted,
-                                                          int32_t* __restrict__ out_tokens,
-                                                          int32_t* __restrict__ n_emitted,
-                                                          uint32_t* __restrict__ near_tie) {
-  __shared__ float s_mx[4], s_sum[4];
-  __shared__ int s_arg[4];
-  __shared__ float s_lse[BS_MAX_K + 1];
-  __shared__ int s_argmax[BS_MAX_K + 1];
-  const int b = blockIdx.x, tid = threadIdx.x;
+// One thread per sequence: the first rejected draft, the row that will be sampled from and how.
+__global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_max, int dense_q, float temperature,
+                                                         int eos_id, int emit_bonus, const float* __restrict__ u_accept,
+                                                         SamplerBufs sb, int32_t* __restrict__ n_accepted,
+                                                         int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
+                                                         uint32_t* __restrict__ near_tie) {
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  if (b >= B) return;
   const int k = p.seq_k[b];
   int32_t* out = out_tokens + (size_t)b * (k_max + 1);
   if (k < 0) {                                      // sequence skipped by the plan
-    if (tid == 0) { n_accepted[b] = 0; n_emitted[b] = 0; near_tie[b] = 0; sb.sel_mode[b] = MODE_NONE; sb.sel_row[b] = 0; }
-    for (int i = tid; i <= k_max; i += 256) out[i] = -1;
+    n_accepted[b] = 0; n_emitted[b] = 0; near_tie[b] = 0; sb.sel_mode[b] = MODE_NONE; sb.sel_row[b] = 0;
+    for (int i = 0; i <= k_max; ++i) out[i] = -1;
     return;
   }
   const int r0 = p.row_start[b];
   const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
-  for (int i = 0; i <= k; ++i) {                    // combine the per-tile statistics of row i
-    const int r = r0 + i;
-    float mx = -INFINITY;
-    int arg = 0x7fffffff;
-    for (int vt = tid; vt < n_vtiles; vt += 256) {
-      float m2 = sb.part_max[(size_t)vt * M_max + r];
-      int a2 = sb.part_arg[(size_t)vt * M_max + r];
-      if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-      float mo = __shfl_xor(mx, o);
-      int ao = __shfl_xor(arg, o);
-      if (mo > mx || (mo == mx && ao < arg)) { mx = mo; arg = ao; }
-    }
-    if ((tid & 63) == 0) { s_mx[tid >> 6] = mx; s_arg[tid >> 6] = arg; }
-    __syncthreads();
-    mx = s_mx[0]; arg = s_arg[0];
-    for (int w = 1; w < 4; ++w)
-      if (s_mx[w] > mx || (s_mx[w] == mx && s_arg[w] < arg)) { mx = s_mx[w]; arg = s_arg[w]; }
-    float sum = 0.f;
-    for (int vt = tid; vt < n_vtiles; vt += 256) {
-      float m2 = sb.part_max[(size_t)vt * M_max + r];
-      if (m2 > -INFINITY) sum += sb.part_sum[(size_t)vt * M_max + r] * __expf((m2 - mx) * inv_temp);
-    }
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
-    __syncthreads();
-    if (tid == 0) {
-      s_lse[i] = mx * inv_temp + logf(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
-      s_argmax[i] = arg;
-    }
-    __syncthreads();
-  }
-  if (tid != 0) return;
   int n_acc = 0, mode = MODE_NONE, sel = r0, sel_tok = -1, n_out = 0;
   uint32_t tie = 0;
-  bool stopped = false;
+  bool stopped = false, eos = false;
   for (int i = 0; i < k && !stopped; ++i) {
     const int r = r0 + i;
     const int x = p.row_target[r];
     float px;
-    if (temperature > 0.f) px = __expf(sb.z_target[r] * inv_temp - s_lse[i]);
-    else px = (x == s_argmax[i]) ? 1.0f : 0.0f;
+    if (temperature > 0.f) px = __expf(sb.z_target[r] * inv_temp - sb.row_lse[r]);
+    else px = (x == sb.row_arg[r]) ? 1.0f : 0.0f;
     float rho = px;
     if (dense_q) {
-      float qx = __expf(sb.q_target[r] - sb.q_lse[r]);
+      const float qx = __expf(sb.q_target[r] - sb.q_lse[r]);
       rho = (qx == 0.f) ? INFINITY : px / qx;
     }
     const float u = u_accept[(size_t)b * k_max + i];
@@ -270,19 +296,19 @@ __global__ void __launch_bounds__(256) accept_scan_kernel(Plan p, int k_max, int
     if (u < fminf(1.0f, rho)) {
       out[n_out++] = x;
       ++n_acc;
-      if (x == eos_id) stopped = true;
+      if (x == eos_id) { stopped = true; eos = true; }
     } else {
       sel = r; sel_tok = x;
       mode = dense_q ? MODE_RESID_DENSE : MODE_RESID_ONEHOT;
       stopped = true;
     }
   }
-  if (mode == MODE_NONE && !(n_acc > 0 && out[n_acc - 1] == eos_id) && (emit_bonus || k == 0)) {
+  if (mode == MODE_NONE && !eos && (emit_bonus || k == 0)) {
     sel = r0 + k;
     mode = MODE_PLAIN;
   }
   if (mode != MODE_NONE && temperature == 0.f) {    // one-hot target: every sampled token is the arg-max
-    out[n_out++] = s_argmax[sel - r0];
+    out[n_out++] = sb.row_arg[sel];
     mode = MODE_NONE;
   }
   for (int i = n_out; i <= k_max; ++i) out[i] = -1;
@@ -293,96 +319,157 @@ __global__ void __launch_bounds__(256) accept_scan_kernel(Plan p, int k_max, int
   sb.sel_mode[b] = mode;
   sb.sel_tok[b] = sel_tok;
   sb.sel_qrow[b] = p.draft_start[b] + (sel - r0);
+  sb.sel_pmax[b] = sb.row_max[sel];
+  sb.sel_qmax[b] = (mode == MODE_RESID_DENSE) ? sb.q_max[sel] : 0.f;
 }
 
 // ------------------------------------------------------------------ inverse-CDF sampling (Eq. 3)
-// One workgroup of 1024 threads per sequence; thread t owns a contiguous slice of the vocabulary.
+// The vocabulary of each sampled row is cut into kSampleChunks chunks so that B x 32 workgroups share
+// the float64 exponentials.  Three small kernels: normaliser partials, chunk masses, pick.
+//   p_j = exp(z_j/T - max) / sum_p ;  q_j likewise ;  w_j = p_j | p_j [j != draft] | max(0, p_j - q_j)
 template <typename Q>
-__global__ void __launch_bounds__(1024) sample_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                      const Q* __restrict__ q_logits, float temperature,
-                                                      const float* __restrict__ u_sample, SamplerBufs sb,
-                                                      const int32_t* __restrict__ n_accepted, int k_max,
-                                                      int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
-                                                      uint32_t* __restrict__ near_tie) {
-  __shared__ double s_d[16];
-  __shared__ double s_scan[1024];
+struct SampleRow {
+  const float* z; const Q* q; double T, mxp, mxq; int tgt, mode;
+  __device__ double e_p(int j) const { return exp((double)z[j] / T - mxp); }
+  __device__ double e_q(int j) const { return exp((double)to_f32<Q>(q[j]) - mxq); }
+  __device__ double weight(int j, double sp, double sq, int mode_now) const {
+    const double pj = e_p(j) / sp;
+    if (mode_now == MODE_PLAIN) return pj;
+    if (mode_now == MODE_RESID_ONEHOT) return j == tgt ? 0.0 : pj;
+    return fmax(0.0, pj - e_q(j) / sq);
+  }
+};
+
+template <typename Q>
+__device__ __forceinline__ SampleRow<Q> sample_row(int b, int V, const float* logit_base, int rows_are_selected,
+                                                   const Q* q_logits, float temperature, const SamplerBufs& sb) {
+  SampleRow<Q> r;
+  r.mode = sb.sel_mode[b];
+  r.z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
+  r.q = (r.mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
+  r.T = (double)temperature;
+  r.mxp = (double)sb.sel_pmax[b] / r.T;              // max_j z_j/T: division is monotone
+  r.mxq = (double)sb.sel_qmax[b];
+  r.tgt = sb.sel_tok[b];
+  return r;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {     // 256 threads
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <typename Q>
+__global__ void __launch_bounds__(256) sample_sum_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
+                                                         const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
+  __shared__ double red[4];
+  const int c = blockIdx.x, b = blockIdx.y;
+  if (sb.sel_mode[b] == MODE_NONE) return;
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
+  const int j0 = min(c * chunk, V), j1 = min(j0 + chunk, V);
+  double sp = 0.0, sq = 0.0;
+  for (int j = j0 + threadIdx.x; j < j1; j += 256) {
+    sp += r.e_p(j);
+    if (r.q) sq += r.e_q(j);
+  }
+  sp = block_sum_f64(sp, red);
+  sq = block_sum_f64(sq, red);
+  if (threadIdx.x == 0) {
+    sb.samp_sum[((size_t)b * kSampleChunks + c) * 2] = sp;
+    sb.samp_sum[((size_t)b * kSampleChunks + c) * 2 + 1] = sq;
+  }
+}
+
+__device__ __forceinline__ void sample_totals(const SamplerBufs& sb, int b, double& sp, double& sq) {
+  sp = 0.0; sq = 0.0;
+  for (int c = 0; c < kSampleChunks; ++c) {          // fixed order: every workgroup gets the same totals
+    sp += sb.samp_sum[((size_t)b * kSampleChunks + c) * 2];
+    sq += sb.samp_sum[((size_t)b * kSampleChunks + c) * 2 + 1];
+  }
+}
+
+// chunk masses of the residual (index 0) and of p itself (index 1, used when the residual is empty)
+template <typename Q>
+__global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
+                                                          const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
+  __shared__ double red[4];
+  const int c = blockIdx.x, b = blockIdx.y;
+  if (sb.sel_mode[b] == MODE_NONE) return;
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  double sp, sq;
+  sample_totals(sb, b, sp, sq);
+  const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
+  const int j0 = min(c * chunk, V), j1 = min(j0 + chunk, V);
+  double mw = 0.0, mp = 0.0;
+  for (int j = j0 + threadIdx.x; j < j1; j += 256) {
+    mw += r.weight(j, sp, sq, r.mode);
+    mp += r.e_p(j) / sp;
+  }
+  mw = block_sum_f64(mw, red);
+  mp = block_sum_f64(mp, red);
+  if (threadIdx.x == 0) {
+    sb.samp_mass[((size_t)b * kSampleChunks + c) * 2] = mw;
+    sb.samp_mass[((size_t)b * kSampleChunks + c) * 2 + 1] = mp;
+  }
+}
+
+template <typename Q>
+__global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
+                                                          const Q* __restrict__ q_logits, float temperature,
+                                                          const float* __restrict__ u_sample, SamplerBufs sb,
+                                                          const int32_t* __restrict__ n_accepted, int k_max,
+                                                          int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
+                                                          uint32_t* __restrict__ near_tie) {
+  __shared__ double s_scan[256];
   __shared__ int s_i[2];
   const int b = blockIdx.x, tid = threadIdx.x;
-  int mode = sb.sel_mode[b];
-  if (mode == MODE_NONE) return;
-  const float* z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
-  const Q* q = (mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
-  const int tgt = sb.sel_tok[b];
-  const double T = (double)temperature;
-  const int chunk = (V + 1023) / 1024;
-  const int j0 = min(tid * chunk, V), j1 = min(j0 + chunk, V);
-
-  auto block_max = [&](double v) {
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-    __syncthreads();
-    if ((tid & 63) == 0) s_d[tid >> 6] = v;
-    __syncthreads();
-    double r = s_d[0];
-    for (int w = 1; w < 16; ++w) r = fmax(r, s_d[w]);
-    return r;
-  };
-  auto block_sum = [&](double v) {
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    __syncthreads();
-    if ((tid & 63) == 0) s_d[tid >> 6] = v;
-    __syncthreads();
-    double r = 0.0;
-    for (int w = 0; w < 16; ++w) r += s_d[w];
-    return r;
-  };
-
-  // pass A: normalisers of p (and q)
-  double mxp = -INFINITY, mxq = -INFINITY;
-  for (int j = j0; j < j1; ++j) {
-    mxp = fmax(mxp, (double)z[j] / T);
-    if (q) mxq = fmax(mxq, (double)to_f32<Q>(q[j]));
+  if (sb.sel_mode[b] == MODE_NONE) return;
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  double sp, sq;
+  sample_totals(sb, b, sp, sq);
+  // chunk level (every thread walks the 32 chunk masses: same result in all threads)
+  int mode = r.mode;
+  double total = 0.0;
+  for (int c = 0; c < kSampleChunks; ++c) total += sb.samp_mass[((size_t)b * kSampleChunks + c) * 2];
+  if (!(total > 0.0) && mode != MODE_PLAIN) {       // empty residual: fall back to the target itself
+    mode = MODE_PLAIN;
+    total = 0.0;
+    for (int c = 0; c < kSampleChunks; ++c) total += sb.samp_mass[((size_t)b * kSampleChunks + c) * 2 + 1];
   }
-  mxp = block_max(mxp);
-  if (q) mxq = block_max(mxq);
-  double sp = 0.0, sq = 0.0;
-  for (int j = j0; j < j1; ++j) {
-    sp += exp((double)z[j] / T - mxp);
-    if (q) sq += exp((double)to_f32<Q>(q[j]) - mxq);
-  }
-  sp = block_sum(sp);
-  if (q) sq = block_sum(sq);
-
-  auto weight = [&](int j) -> double {
-    double pj = exp((double)z[j] / T - mxp) / sp;
-    if (mode == MODE_PLAIN) return pj;
-    if (mode == MODE_RESID_ONEHOT) return j == tgt ? 0.0 : pj;
-    double qj = exp((double)to_f32<Q>(q[j]) - mxq) / sq;
-    return fmax(0.0, pj - qj);
-  };
-
-  double csum, total;
-  for (;;) {
-    // pass B: slice sums and their inclusive scan
-    csum = 0.0;
-    for (int j = j0; j < j1; ++j) csum += weight(j);
-    s_scan[tid] = csum;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-      double v = (tid >= o) ? s_scan[tid - o] : 0.0;
-      __syncthreads();
-      s_scan[tid] += v;
-      __syncthreads();
-    }
-    total = s_scan[1023];
-    if (total > 0.0 || mode == MODE_PLAIN) break;
-    mode = MODE_PLAIN;                              // empty residual: fall back to the target itself
-    __syncthreads();
-  }
-  const double incl = s_scan[tid], excl = incl - csum;
+  const int mi = (mode == r.mode) ? 0 : 1;
   const double t = (double)u_sample[b] * total;
+  int cs = -1, last_c = -1;
+  double excl_c = 0.0, run = 0.0, last_excl = 0.0;
+  for (int c = 0; c < kSampleChunks; ++c) {
+    const double m = sb.samp_mass[((size_t)b * kSampleChunks + c) * 2 + mi];
+    if (m > 0.0) { last_c = c; last_excl = run; }
+    if (cs < 0 && run + m > t) { cs = c; excl_c = run; }
+    run += m;
+  }
+  if (cs < 0) { cs = last_c; excl_c = last_excl; }  // rounding left no chunk: last chunk with weight
+  if (cs < 0) return;                               // no weight anywhere (cannot happen for finite logits)
+  // slice level inside the chosen chunk
+  const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
+  const int c0 = min(cs * chunk, V), c1 = min(c0 + chunk, V);
+  const int slice = (c1 - c0 + 255) / 256;
+  const int j0 = min(c0 + tid * slice, c1), j1 = min(j0 + slice, c1);
+  double csum = 0.0;
+  for (int j = j0; j < j1; ++j) csum += r.weight(j, sp, sq, mode);
+  s_scan[tid] = csum;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const double v = (tid >= o) ? s_scan[tid - o] : 0.0;
+    __syncthreads();
+    s_scan[tid] += v;
+    __syncthreads();
+  }
+  const double incl = excl_c + s_scan[tid], excl = incl - csum;
   if (tid == 0) { s_i[0] = 0x7fffffff; s_i[1] = -1; }
   __syncthreads();
-  // owner = first slice whose inclusive sum exceeds t; fallback = last slice with weight
   if (csum > 0.0) {
     if (incl > t && excl <= t) atomicMin(&s_i[0], tid);
     atomicMax(&s_i[1], tid);
@@ -390,41 +477,50 @@ __global__ void __launch_bounds__(1024) sample_kernel(int V, const float* __rest
   __syncthreads();
   const int owner = (s_i[0] != 0x7fffffff) ? s_i[0] : s_i[1];
   if (tid != owner) return;
-  double run = excl, w = 0.0;
+  double acc = excl, w = 0.0, last_hi = 0.0, last_w = 0.0;
   int tok = -1, last = -1;
-  double last_hi = 0.0, last_w = 0.0;
   for (int j = j0; j < j1; ++j) {
-    w = weight(j);
-    run += w;
-    if (w > 0.0) { last = j; last_hi = run; last_w = w; }
-    if (run > t) { tok = j; break; }
+    w = r.weight(j, sp, sq, mode);
+    acc += w;
+    if (w > 0.0) { last = j; last_hi = acc; last_w = w; }
+    if (acc > t) { tok = j; break; }
   }
-  if (tok < 0) { tok = last; run = last_hi; w = last_w; }
+  if (tok < 0) { tok = last; acc = last_hi; w = last_w; }
   const int n_acc = n_accepted[b];
   out_tokens[(size_t)b * (k_max + 1) + n_acc] = tok;
   n_emitted[b] = n_acc + 1;
-  const double lo = run - w;
-  if (fmin(fabs(t - lo), fabs(run - t)) <= 1e-3 * w) near_tie[b] |= 0x80000000u;
+  const double lo = acc - w;
+  if (fmin(fabs(t - lo), fabs(acc - t)) <= 1e-3 * w) near_tie[b] |= 0x80000000u;
 }
 
 // ------------------------------------------------------------------ launchers
-void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head, float inv_temp,
-                         const SamplerBufs& sb, float* logits_debug, hipStream_t st) {
-  using G = MfmaGemm<kLmMT, kLmNT, true>;
+template <int MT, bool STATS>
+static void launch_lmhead_t(const Shape& s, const int32_t* n_rows_dev, int M_max, const void* hf, const int32_t* x_rows,
+                            const void* lm_head, float inv_temp, const int32_t* row_target, const SamplerBufs& sb,
+                            float* store, hipStream_t st) {
+  using G = MfmaGemm<MT, kLmNT, true>;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
   int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
-  hipLaunchKernelGGL(lmhead_kernel<true>, dim3(grid), dim3(256), G::LDS_BYTES, st, p.n_rows, M_max, s.V, s.d,
-                     (const f16*)hf, (const int32_t*)nullptr, (const f16*)lm_head, inv_temp, p.row_target, sb,
-                     logits_debug, m_blocks, n_blocks);
+  hipLaunchKernelGGL((lmhead_kernel<MT, STATS>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, s.V, s.d,
+                     (const f16*)hf, x_rows, (const f16*)lm_head, inv_temp, row_target, sb, store, m_blocks, n_blocks);
+}
+template <bool STATS>
+static void launch_lmhead_any(const Shape& s, const int32_t* n_rows_dev, int M_max, const void* hf, const int32_t* x_rows,
+                              const void* lm_head, float inv_temp, const int32_t* row_target, const SamplerBufs& sb,
+                              float* store, hipStream_t st) {
+  if (M_max <= 32) launch_lmhead_t<1, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
+  else if (M_max <= 64) launch_lmhead_t<2, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
+  else if (M_max <= 128 || (M_max + 127) / 128 * 128 < (M_max + 191) / 192 * 192)
+    launch_lmhead_t<4, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
+  else launch_lmhead_t<6, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
+}
+void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head, float inv_temp,
+                         const SamplerBufs& sb, float* logits_debug, hipStream_t st) {
+  launch_lmhead_any<true>(s, p.n_rows, M_max, hf, nullptr, lm_head, inv_temp, p.row_target, sb, logits_debug, st);
 }
 void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_head, const SamplerBufs& sb,
                         hipStream_t st) {
-  using G = MfmaGemm<kLmMT, kLmNT, true>;
-  int m_blocks = (B + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
-  int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
-  hipLaunchKernelGGL(lmhead_kernel<false>, dim3(grid), dim3(256), G::LDS_BYTES, st, (const int32_t*)nullptr, B, s.V, s.d,
-                     (const f16*)hf, sb.sel_row, (const f16*)lm_head, 1.0f, (const int32_t*)nullptr, sb,
-                     sb.sel_logits, m_blocks, n_blocks);
+  launch_lmhead_any<false>(s, nullptr, B, hf, sb.sel_row, lm_head, 1.0f, nullptr, sb, sb.sel_logits, st);
 }
 void launch_logit_stats(const Plan& p, int M_max, int V, const float* logits, float inv_temp, const SamplerBufs& sb,
                         hipStream_t st) {
@@ -439,8 +535,20 @@ void launch_q_stats(const Plan& p, int M_max, int V, const void* q_logits, int q
 void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles, bool dense_q, float temperature,
                         int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
                         int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
-  hipLaunchKernelGGL(accept_scan_kernel, dim3(B), dim3(256), 0, st, p, k_max, M_max, n_vtiles, dense_q ? 1 : 0,
-                     temperature, eos_id, emit_bonus, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
+  const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
+  hipLaunchKernelGGL(row_stats_kernel, dim3(M_max), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb);
+  hipLaunchKernelGGL(accept_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, st, p, B, k_max, dense_q ? 1 : 0, temperature,
+                     eos_id, emit_bonus, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
+}
+template <typename Q>
+static void launch_sample_t(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const Q* q_logits,
+                            float temperature, const float* u_sample, const SamplerBufs& sb, const int32_t* n_accepted,
+                            int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
+  const int sel = rows_are_selected ? 1 : 0;
+  hipLaunchKernelGGL(sample_sum_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
+  hipLaunchKernelGGL(sample_mass_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
+  hipLaunchKernelGGL(sample_pick_kernel<Q>, dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, u_sample, sb,
+                     n_accepted, k_max, out_tokens, n_emitted, near_tie);
 }
 void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
                    int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
@@ -448,9 +556,9 @@ void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_a
                    hipStream_t st) {
   if (temperature == 0.f) return;                    // the scan already emitted the arg-max tokens
   if (q_logits && q_dtype == BS_BF16)
-    hipLaunchKernelGGL(sample_kernel<bf16>, dim3(B), dim3(1024), 0, st, V, logit_base, rows_are_selected ? 1 : 0,
-                       (const bf16*)q_logits, temperature, u_sample, sb, n_accepted, k_max, out_tokens, n_emitted, near_tie);
+    launch_sample_t<bf16>(B, k_max, V, logit_base, rows_are_selected, (const bf16*)q_logits, temperature, u_sample, sb,
+                          n_accepted, out_tokens, n_emitted, near_tie, st);
   else
-    hipLaunchKernelGGL(sample_kernel<float>, dim3(B), dim3(1024), 0, st, V, logit_base, rows_are_selected ? 1 : 0,
-                       (const float*)q_logits, temperature, u_sample, sb, n_accepted, k_max, out_tokens, n_emitted, near_tie);
+    launch_sample_t<float>(B, k_max, V, logit_base, rows_are_selected, (const float*)q_logits, temperature, u_sample, sb,
+                           n_accepted, out_tokens, n_emitted, near_tie, st);
 }
