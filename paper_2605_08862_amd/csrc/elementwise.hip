@@ -35,16 +35,20 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
   if (r >= p.n_rows[0]) return;
   float* x = h + (size_t)r * d;
   float ss = 0.f;
-  if (n_slabs > 0) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  if (n_slabs > 0) {                       // d is a multiple of 64: 16-byte accesses throughout
     const float* sl = slabs + (size_t)r * d;
-    for (int i = threadIdx.x; i < d; i += 256) {
-      float v = x[i];
-      for (int s = 0; s < n_slabs; ++s) v += sl[(size_t)s * slab_stride + i];
-      x[i] = v;
-      ss += v * v;
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      f4 v = *(const f4*)(x + i);
+      for (int s = 0; s < n_slabs; ++s) v += *(const f4*)(sl + (size_t)s * slab_stride + i);
+      *(f4*)(x + i) = v;
+      ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     }
   } else {
-    for (int i = threadIdx.x; i < d; i += 256) { float v = x[i]; ss += v * v; }
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      const f4 v = *(const f4*)(x + i);
+      ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    }
   }
   ss = block_sum_256(ss, red);
   float inv = 1.0f / sqrtf(ss / (float)d + eps);

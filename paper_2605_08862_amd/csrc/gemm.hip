@@ -115,7 +115,7 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 // [M_max, N] slab per K split, out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums
 // the slabs.  Float atomics into the residual were measured at ~25 us per launch and are not used.
 template <int MT, int NT, int EPI>
-__global__ void __launch_bounds__(256) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
+__global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
                                                         int m_blocks, int n_blocks) {
@@ -249,7 +249,12 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return 0; }
   static const char* env_split = getenv("BS_GEMM_SPLIT");          // tuning aids
   static const char* env_nt = getenv("BS_GEMM_NT");
-  const int mt = pick_mt(M_max);
+  static const char* env_mt = getenv("BS_GEMM_MT");
+  int mt = pick_mt(M_max);
+  // float32-epilogue GEMMs have narrow outputs (N = d or Nqkv): measured on MI355X at M = 576, smaller row
+  // tiles with at most 4 K splits beat 192-row tiles with 7 splits (down projection 50 -> 33 us, O 17 -> 13 us)
+  if ((EPI == EPI_RESID_ADD || EPI == EPI_STORE_F32) && M_max > 64) mt = (K / kBK <= 32) ? 2 : 4;
+  if (env_mt) mt = atoi(env_mt);
   const int m_blocks = (M_max + mt * 32 - 1) / (mt * 32);
   int nt = 2;
   if (EPI != EPI_SWIGLU) {
@@ -266,17 +271,18 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
     if (n_split > nk / 4) n_split = nk / 4 > 0 ? nk / 4 : 1;       // at least 4 K tiles per split
     if (env_split) n_split = atoi(env_split);
     if (n_split < 1) n_split = 1;
+    if (n_split > 4 && !env_split) n_split = 4;
     if (n_split > kMaxGemmSplit) n_split = kMaxGemmSplit;
     if (n_split > nk) n_split = nk;
   }
 #define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
   if constexpr (EPI != EPI_SWIGLU) {
     if (nt == 1) {
-      switch (mt) { case 1: BS_GEMM(1, 1); break; case 2: BS_GEMM(2, 1); break; case 4: BS_GEMM(4, 1); break; default: BS_GEMM(6, 1); }
+      switch (mt) { case 1: BS_GEMM(1, 1); break; case 2: BS_GEMM(2, 1); break; case 3: BS_GEMM(3, 1); break; case 4: BS_GEMM(4, 1); break; default: BS_GEMM(6, 1); }
       return n_split;
     }
   }
-  switch (mt) { case 1: BS_GEMM(1, 2); break; case 2: BS_GEMM(2, 2); break; case 4: BS_GEMM(4, 2); break; default: BS_GEMM(6, 2); }
+  switch (mt) { case 1: BS_GEMM(1, 2); break; case 2: BS_GEMM(2, 2); break; case 3: BS_GEMM(3, 2); break; case 4: BS_GEMM(4, 2); break; default: BS_GEMM(6, 2); }
 #undef BS_GEMM
   return n_split;
 }
