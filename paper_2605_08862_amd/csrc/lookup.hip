@@ -15,12 +15,13 @@ namespace {
 constexpr int kCap = 1024;     // occurrences kept in LDS; beyond that the pool is rescanned per step
 constexpr int kHash = 4096;    // hash slots (token, count)
 constexpr int kMaxMatch = 8;
+constexpr int kThreads = 1024;  // one workgroup per sequence: many loads in flight hide the pool's latency
 
 struct Best { int cnt; int tok; };
 __device__ __forceinline__ bool better(int c1, int t1, int c2, int t2) { return c1 > c2 || (c1 == c2 && t1 < t2); }
 }  // namespace
 
-__global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_t* __restrict__ pool,
+__global__ void __launch_bounds__(kThreads) lookup_kernel(int n_prompts, const int32_t* __restrict__ pool,
                                                      const int64_t* __restrict__ ro, const int32_t* __restrict__ prb,
                                                      const int32_t* __restrict__ seq_prompt,
                                                      const int32_t* __restrict__ tail, int max_match, int min_match,
@@ -35,7 +36,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
   __shared__ int s_draft[BS_MAX_K + 1];
   const int b = blockIdx.x, tid = threadIdx.x;
   int32_t* out = draft_tokens + (size_t)b * k_max;
-  for (int i = tid; i < k_max; i += 256) out[i] = -1;
+  for (int i = tid; i < k_max; i += kThreads) out[i] = -1;
   const int pr = seq_prompt[b];
   if (pr < 0 || pr >= n_prompts || k_max == 0) { if (tid == 0) draft_len[b] = 0; return; }
   const int r_begin = prb[pr], r_end = prb[pr + 1];
@@ -52,12 +53,20 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
     while (len < mm && e - len >= s0 && pool[e - len] == s_ctx[max_match - 1 - len]) ++len;
     return len;
   };
-  // phase 1: histogram of match lengths
+  // phase 1 (one pass over the pool): histogram of match lengths; every occurrence of at least
+  // min_match tokens is also kept (with its length) while the list has room, so that the usual case
+  // needs no second pass
+  if (tid == 0) { s_ncand[0] = 0; s_ncand[1] = 0; }
+  __syncthreads();
   for (int r = r_begin; r < r_end; ++r) {
     const long long s0 = ro[r], s1 = ro[r + 1];
-    for (long long e = s0 + tid; e < s1; e += 256) {
+    for (long long e = s0 + tid; e < s1; e += kThreads) {
       int len = match_len(e, s0);
-      if (len >= min_match) atomicAdd(&s_cnt[len], 1);
+      if (len >= min_match) {
+        atomicAdd(&s_cnt[len], 1);
+        int i = atomicAdd(&s_ncand[1], 1);             // total count (may exceed the capacity)
+        if (i < kCap) { s_pos[1][i] = (int)(e - base); s_end[1][i] = (int)(s1 - base); s_htok[i] = len; }
+      }
     }
   }
   __syncthreads();
@@ -68,17 +77,26 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
   }
   if (m_star == 0) { if (tid == 0) draft_len[b] = 0; return; }
   const bool list_mode = n0 <= kCap;
-  if (tid == 0) { s_ncand[0] = 0; s_ncand[1] = 0; }
+  const int n_all = s_ncand[1];
   __syncthreads();
   if (list_mode) {
-    for (int r = r_begin; r < r_end; ++r) {
-      const long long s0 = ro[r], s1 = ro[r + 1];
-      for (long long e = s0 + tid; e < s1; e += 256)
-        if (match_len(e, s0) >= m_star) {
-          int i = atomicAdd(&s_ncand[0], 1);
-          s_pos[0][i] = (int)(e - base);
-          s_end[0][i] = (int)(s1 - base);
+    if (n_all <= kCap) {                                // filter the kept occurrences by the chosen length
+      for (int i = tid; i < n_all; i += kThreads)
+        if (s_htok[i] >= m_star) {
+          int o = atomicAdd(&s_ncand[0], 1);
+          s_pos[0][o] = s_pos[1][i];
+          s_end[0][o] = s_end[1][i];
         }
+    } else {                                            // the kept list overflowed: second pass for m_star only
+      for (int r = r_begin; r < r_end; ++r) {
+        const long long s0 = ro[r], s1 = ro[r + 1];
+        for (long long e = s0 + tid; e < s1; e += kThreads)
+          if (match_len(e, s0) >= m_star) {
+            int i = atomicAdd(&s_ncand[0], 1);
+            s_pos[0][i] = (int)(e - base);
+            s_end[0][i] = (int)(s1 - base);
+          }
+      }
     }
     __syncthreads();
   }
@@ -88,14 +106,14 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
     // enumerate the successor token of every surviving occurrence
     auto for_each_succ = [&](auto f) {
       if (list_mode) {
-        for (int i = tid; i < s_ncand[cur]; i += 256) {
+        for (int i = tid; i < s_ncand[cur]; i += kThreads) {
           int e = s_pos[cur][i];
           if (e + 1 < s_end[cur][i]) f(pool[base + e + 1]);
         }
       } else {
         for (int r = r_begin; r < r_end; ++r) {
           const long long s0 = ro[r], s1 = ro[r + 1];
-          for (long long e = s0 + tid; e + j + 1 < s1; e += 256) {
+          for (long long e = s0 + tid; e + j + 1 < s1; e += kThreads) {
             if (match_len(e, s0) < m_star) continue;
             bool ok = true;
             for (int i = 0; i < j && ok; ++i) ok = pool[e + 1 + i] == s_draft[i];
@@ -110,7 +128,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
       bool overflow = false;
       best_cnt = 0; best_tok = 0x7fffffff;
       for (int cls = 0; cls < P; ++cls) {
-        for (int i = tid; i < kHash; i += 256) { s_htok[i] = -1; s_hcnt[i] = 0; }
+        for (int i = tid; i < kHash; i += kThreads) { s_htok[i] = -1; s_hcnt[i] = 0; }
         if (tid == 0) { s_flag = 0; s_best_cnt = 0; s_best_tok = 0x7fffffff; }
         __syncthreads();
         for_each_succ([&](int t) {
@@ -127,7 +145,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
         if (s_flag) { overflow = true; }
         // reduce the table (each thread its slots, then one atomic round through LDS)
         int c = 0, t = 0x7fffffff;
-        for (int i = tid; i < kHash; i += 256)
+        for (int i = tid; i < kHash; i += kThreads)
           if (s_htok[i] >= 0 && better(s_hcnt[i], s_htok[i], c, t)) { c = s_hcnt[i]; t = s_htok[i]; }
         if (c > 0) atomicMax(&s_best_cnt, c);
         __syncthreads();
@@ -146,7 +164,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
       const int nxt = cur ^ 1;
       if (tid == 0) s_ncand[nxt] = 0;
       __syncthreads();
-      for (int i = tid; i < s_ncand[cur]; i += 256) {
+      for (int i = tid; i < s_ncand[cur]; i += kThreads) {
         int e = s_pos[cur][i];
         if (e + 1 < s_end[cur][i] && pool[base + e + 1] == best_tok) {
           int o = atomicAdd(&s_ncand[nxt], 1);
@@ -164,6 +182,6 @@ __global__ void __launch_bounds__(256) lookup_kernel(int n_prompts, const int32_
 void launch_lookup(int B, int n_prompts, const int32_t* pool_tokens, const int64_t* rollout_offsets,
                    const int32_t* prompt_rollout_begin, const int32_t* seq_prompt, const int32_t* tail, int max_match,
                    int min_match, int k_max, int32_t* draft_tokens, int32_t* draft_len, hipStream_t st) {
-  hipLaunchKernelGGL(lookup_kernel, dim3(B), dim3(256), 0, st, n_prompts, pool_tokens, rollout_offsets,
+  hipLaunchKernelGGL(lookup_kernel, dim3(B), dim3(kThreads), 0, st, n_prompts, pool_tokens, rollout_offsets,
                      prompt_rollout_begin, seq_prompt, tail, max_match, min_match, k_max, draft_tokens, draft_len);
 }
