@@ -27,6 +27,9 @@ from paper_2605_08862_amd.runtime import Engine, fuse_weights  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 AGREEMENT_NOISE = 0.771          # s with 2*Phi(-s/2) = 0.7 (lognormal closed form for E min(p, q))
+# HBM bytes per launch of each kernel class at the DEFAULT workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by a plain copy of known size; see profiles/bench_s1p5b_b64_c2048_k8_kernels.txt).  Other workloads: null.
+MEASURED_TRAFFIC_BYTES = {"gemm_gate_up": 69.4e6 + 10.3e6, "gemm_down": 121.7e6 + 14.2e6, "attention": 138.5e6 + 7.2e6}
 
 
 def build_workload(args):
@@ -129,6 +132,9 @@ def main():
     ap.add_argument("--k", type=int, default=8)
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (known traffic) for calibrating rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (sequences shard across GPUs with no collective on the "
@@ -136,6 +142,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     wl = build_workload(args)
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         out = one_step(wl)
     torch.cuda.synchronize()
@@ -210,8 +222,10 @@ def measure_roofline(wl, args):
             t = per_class[c]["us_per_launch"] * 1e-6
             per_class[c]["bound"] = bnd
             per_class[c]["frac_of_peak"] = (u / t / 1e9 / HBM_PEAK_GBS) if bnd == "hbm" else (u / t / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+    default_wl = (args.batch, args.context, args.k, args.layers) == (64, 2048, 8, 28)
+    traffic = MEASURED_TRAFFIC_BYTES.get(dom) if default_wl else None
     return {"roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                         "frac": achieved / peak, "traffic": None,
+                         "frac": achieved / peak, "traffic": traffic,
                          "us_per_launch": per_class[dom]["us_per_launch"]},
             "kernel_classes": per_class}
 
