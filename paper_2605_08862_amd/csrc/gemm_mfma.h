@@ -98,71 +98,55 @@ struct MfmaGemm {
   template <int STAGE>
   __device__ static __forceinline__ void load_x(u32x4 (&xreg)[3][MT], const Operands& op, int kt) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-#ifdef BS_DBG_NOX
-      if (kt > 0) continue;
-#endif
-      xreg[STAGE][i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt * kBK);
-    }
+    for (int i = 0; i < MT; ++i) xreg[STAGE][i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt * kBK);
   }
 
   // One K tile.  STAGE = (kt - kt0) % 3 names the register ring slots: weights of tile j live in
   // wreg[j % 3], activation chunks of tile j in xreg[j % 3] until they are written to LDS stage j & 1.
-  // Both streams are requested two iterations before they are needed: measured on MI355X, a one-
-  // iteration distance for the activations (L2 / fabric latency ~1-2 us) left the waves waiting on
-  // vmcnt for ~40 % of their lifetime.
+  // Both streams are requested two iterations before they are needed.
+  //
+  // Issue order.  The MFMA pipe runs asynchronously, so the memory instructions of the iteration are
+  // dealt out between the MFMA groups instead of being issued in one burst at the top (14 global loads
+  // alone occupy the address path for ~220 cycles during which a one-wave-per-SIMD kernel would leave
+  // the matrix unit idle).  Slot j = (K-step s, row tile mi) carries: the LDS read of the fragment
+  // needed one K-step later, a share of {LDS store of the next tile's activations, global loads of the
+  // activations three tiles ahead, global loads of the weights two tiles ahead}, then the NT MFMAs of
+  // (s, mi).  Every load and store is UNCONDITIONAL (tile indices are clamped to the last tile): a
+  // prefetch issued under a condition makes the compiler's wait-count tracking assume it may be the
+  // newest outstanding load, and the resulting vmcnt(0) waits serialise the ring.
   template <int STAGE>
   __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[3][MT],
                                               const Operands& op, int kt, int kt1, char* lds) {
     const int lane = threadIdx.x & 63;
-    // Every load and store below is UNCONDITIONAL (tile indices are clamped to the last tile instead):
-    // a prefetch issued under a condition makes the compiler's wait-count tracking assume it may be
-    // the newest outstanding load, and the resulting vmcnt(0) waits serialise the whole ring.
-    {                                                     // activations of the next K tile -> LDS
-      char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-#ifdef BS_DBG_NOLDS
-        if (kt > 0) continue;
-#endif
-        *(u32x4*)(nstage + op.x_lds[i]) = xreg[(STAGE + 1) % 3][i];
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    load_x<STAGE>(xreg, op, min(kt + 3, kt1 - 1));        // slot of tile kt is free (written to LDS last iteration)
-    __builtin_amdgcn_sched_barrier(0);
-    load_w<(STAGE + 2) % 3>(wreg, op, min(kt + 2, kt1 - 1));
-    __builtin_amdgcn_sched_barrier(0);
-    // fragment reads run one K-step ahead of the MFMAs that consume them (LDS latency hidden)
+    constexpr int SLOTS = 4 * MT, EXTRA = 2 * MT + 4 * NT;
     const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
+    char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
+    const int kx = min(kt + 3, kt1 - 1), kw = min(kt + 2, kt1 - 1);
     u32x4 xf[2][MT];
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) xf[0][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, 0, lane));
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s < 3) {
+    for (int j = 0; j < SLOTS; ++j) {
+      const int s = j / MT, mi = j % MT;
+      if (s < 3) xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
 #pragma unroll
-        for (int mi = 0; mi < MT; ++mi) {
-#ifdef BS_DBG_NOLDS
-          xf[(s + 1) & 1][mi] = xf[s & 1][mi];
-#else
-          xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
-#endif
+      for (int e = j * EXTRA / SLOTS; e < (j + 1) * EXTRA / SLOTS; ++e) {
+        if (e < MT) {
+          *(u32x4*)(nstage + op.x_lds[e]) = xreg[(STAGE + 1) % 3][e];
+        } else if (e < 2 * MT) {
+          xreg[STAGE][e - MT] = *(const u32x4*)(op.x_rows[e - MT] + (size_t)kx * kBK);
+        } else {
+          const int ni = (e - 2 * MT) / 4, ws = (e - 2 * MT) % 4;
+          wreg[(STAGE + 2) % 3][ni][ws] = *(const u32x4*)(op.w_tiles[ni] + (size_t)kw * kWBlock + ws * 512);
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
+      const f16x8 x = as_f16x8(xf[s & 1][mi]);
 #pragma unroll
-      for (int mi = 0; mi < MT; ++mi) {
-        const f16x8 x = as_f16x8(xf[s & 1][mi]);
-#pragma unroll
-        for (int ni = 0; ni < NT; ++ni) {
-          const f16x8 wf = as_f16x8(wreg[STAGE][ni][s]);
-#ifdef BS_DBG_NOMFMA
-          if (mi + ni + s > 0) continue;
-#endif
-          if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, x, acc[mi][ni], 0, 0, 0);
-          else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, wf, acc[mi][ni], 0, 0, 0);
-        }
+      for (int ni = 0; ni < NT; ++ni) {
+        const f16x8 wf = as_f16x8(wreg[STAGE][ni][s]);
+        if (SWAP) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, x, acc[mi][ni], 0, 0, 0);
+        else      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, wf, acc[mi][ni], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -184,10 +168,17 @@ struct MfmaGemm {
 #pragma unroll
     for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[0][i];
     __syncthreads();
-    for (int kt = kt0; kt < kt1; kt += 3) {
+    // whole rounds of three tiles without side exits (keeps the register ring free of copies at the
+    // back edge), then the one or two remaining tiles
+    int kt = kt0;
+    for (; kt + 3 <= kt1; kt += 3) {
+      body<0>(acc, wreg, xreg, op, kt, kt1, lds);
+      body<1>(acc, wreg, xreg, op, kt + 1, kt1, lds);
+      body<2>(acc, wreg, xreg, op, kt + 2, kt1, lds);
+    }
+    if (kt < kt1) {
       body<0>(acc, wreg, xreg, op, kt, kt1, lds);
       if (kt + 1 < kt1) body<1>(acc, wreg, xreg, op, kt + 1, kt1, lds);
-      if (kt + 2 < kt1) body<2>(acc, wreg, xreg, op, kt + 2, kt1, lds);
     }
   }
 };
