@@ -195,8 +195,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
       for (int s = 0; s < KS; ++s) kb[s] = ka[s];
 #pragma unroll
       for (int x = 0; x < DT * 2; ++x) vb[x] = va[x];
-      if (t + WPG < t_end) load_tile(t + WPG, ka, va);
-      compute_tile(t, kb, vb);
+      load_tile(t + WPG < t_end ? t + WPG : t, ka, va);   // unconditional (the last one re-reads tile t): a
+      compute_tile(t, kb, vb);                             // conditional prefetch costs vmcnt(0) waits
     }
   }
   __syncthreads();                                      // all waves are done with s_q before s_o reuses it
