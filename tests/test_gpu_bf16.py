@@ -125,3 +125,69 @@ def test_slice_7b_full_vocab():
     """Two layers of the 7B shape (G = 7), full 152064 vocabulary, ragged contexts and draft lengths."""
     desc = W.shape("s7b", n_layers=2)
     _run_case(desc, ctx_lens=[4096, 512, 1800], k_b=[16, 8, 0], k_max=16, seed=27, check_kv=False, q_mode="onehot")
+
+
+def test_slice_7b_long_tail():
+    """Configuration-4 shape on a two-layer 7B slice: contexts from the clipped lognormal range (512 .. 32768),
+    ragged draft lengths 0..16, dense proposals; exercises long KV splits and the four-tile query packing."""
+    desc = W.shape("s7b", n_layers=2)
+    ctx = [512, 3000, 32768 - 17, 9000, 700, 20000]
+    _run_case(desc, ctx_lens=ctx, k_b=[16, 0, 16, 7, 3, 11], k_max=16, seed=28, check_kv=False, q_scale=1.3)
+
+
+def test_lookup_to_commit_without_host_sync():
+    """Configuration-5 flow on a two-layer 1.5B slice: bs_draft_lookup writes draft_tokens / draft_len on the
+    device and bs_verify_step consumes them directly (row packing is planned on the device), then one-hot
+    acceptance (the paper's deterministic-draft rule) and commit.  Checked against the oracle lookup + forward."""
+    from oracle.lookup import lookup as oracle_lookup
+    desc = W.shape("s1p5b", n_layers=2)
+    Bn, k_max, ctx = 16, 16, 300
+    rng = np.random.default_rng(31)
+    V = desc["vocab"]
+    w = W.make_weights(desc, seed=31)
+    wn = _f64_weights(W.weights_to_numpy(w))
+    eng = Engine(desc, fuse_weights(w, desc["dtype"], DEV), Bn, ctx + k_max + 1, B_max=Bn, k_max=k_max, page_perm_seed=5)
+    pool = W.make_pool(32, 2, 8, 2048, V, lo=64, hi=8192)
+    seq_prompt, tails = W.plant_tails(33, pool, Bn, 8, 4, vocab=V)
+    toks, off, prb = pool
+    eng.pool_bind(torch.tensor(toks), torch.tensor(off), torch.tensor(prb))
+    od = H.oracle_desc(desc)
+    caches = []
+    for b in range(Bn):
+        kvs = W.context_kv(desc, ctx, 3100 + b)
+        c = OD.SeqCache(od)
+        c.fill([k.float().numpy() for k, _ in kvs], [v.float().numpy() for _, v in kvs])
+        caches.append(c)
+        for l, (k, v) in enumerate(kvs):
+            eng.kv_write(l, b, 0, k.to(DEV), v.to(DEV))
+    eng.ctx_len.fill_(ctx)
+    last = tails[:, -1].copy()                       # the tail's newest token is the step's last token
+    ua, us = W.uniforms(34, Bn, k_max)
+    slots = H.dev_i32(np.arange(Bn))
+    # device flow: no host read between the calls
+    dt, dl = eng.draft_lookup(H.dev_i32(seq_prompt), H.dev_i32(tails), 4, 1, k_max)
+    logits = eng.verify_step(slots, H.dev_i32(last), dt, dl, k_max, want_logits=True)
+    out = eng.accept_resample(dt, dl, k_max, H.dev_f32(ua), H.dev_f32(us))
+    eng.kv_commit(slots, out["n_accepted"] + 1)
+    assert eng.poll_status() == 0
+    # oracle flow
+    drafts = np.full((Bn, k_max), -1, dtype=np.int64)
+    k_b = np.zeros(Bn, dtype=np.int64)
+    for b in range(Bn):
+        p = seq_prompt[b]
+        ref = oracle_lookup([toks[off[r]:off[r + 1]] for r in range(prb[p], prb[p + 1])], tails[b], 4, 1, k_max)
+        k_b[b] = len(ref)
+        drafts[b, :len(ref)] = ref
+    assert dl.cpu().tolist() == k_b.tolist()
+    assert (dt.cpu().numpy() == drafts).all()
+    assert k_b.max() > 0 and k_b.min() == 0          # both drafted and plain sequences ride in the same launch
+    blocks = H.pack_rows(last, drafts, k_b)
+    ref_logits = np.concatenate([OD.verify_block(od, wn, caches[b], blocks[b]) for b in range(Bn)])
+    M = int(k_b.sum() + Bn)
+    got = logits.cpu().numpy()[:M]
+    assert np.abs(got - ref_logits).max() <= H.TOL_LOGITS[W.BS_BF16]
+    exact, near, _ = H.compare_sampler(out, got, drafts, k_b, ua, us)
+    assert near <= 1
+    n_acc = out["n_accepted"].cpu().numpy()
+    assert eng.ctx_len.cpu().tolist() == [ctx + int(n) + 1 for n in n_acc]
+    eng.close()
