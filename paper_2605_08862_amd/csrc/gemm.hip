@@ -109,24 +109,31 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 // ------------------------------------------------------------------ MFMA kernel (bf16 models)
 // Workgroup tile: BM = 32*MT rows x 4 waves x NT weight row tiles.  For SwiGLU NT == 2 and the two row
 // tiles of a wave are the gate rows and the matching up rows of the same 32 output features, so both
-// land in the same lane.  Grid: x = (M block, N block) pairs, remapped so that the M blocks sharing
-// a weight tile run back to back on one XCD (ids are dealt round-robin to the 8 XCDs) and hit its
-// L2; y = K split.  The float32 epilogues (QKV projection, residual projections) write one partial
+// land in the same lane.  Grid: one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs,
+// each with its own L2, so the id is decoded XCD-first: with S K-splits (S in {1,2,4,8}) a split owns
+// 8/S XCDs, and inside a split each XCD takes a contiguous range of (N block, M block) tiles, M block
+// fastest.  The M blocks that share a weight tile then run back to back on one XCD and hit its L2, and
+// an XCD only ever touches its own K range of the activation matrix (measured before this mapping: the
+// down projection fetched 122 MB per launch for 38 MB of operands, every L2 pulling the whole matrix).  The float32 epilogues (QKV projection, residual projections) write one partial
 // [M_max, N] slab per K split, out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums
 // the slabs.  Float atomics into the residual were measured at ~25 us per launch and are not used.
 template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
-                                                        int m_blocks, int n_blocks) {
+                                                        int m_blocks, int n_blocks, int n_split) {
   // accumulators hold C^T tiles (SWAP): a lane owns one activation row and, per group of four
   // registers, four consecutive output columns, so the epilogue stores 8 or 16 bytes per lane
   using G = MfmaGemm<MT, NT, true>;
   extern __shared__ __align__(16) char lds[];
   const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
   const int total = m_blocks * n_blocks;
-  const int per_xcd = (total + 7) / 8;
-  const int id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int xps = 8 / n_split;                             // XCDs per K split
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int split = xcd / xps;
+  const int per_sub = (total + xps - 1) / xps;
+  if (slot >= per_sub) return;
+  const int id = (xcd % xps) * per_sub + slot;
   if (id >= total) return;
   const int mb = id % m_blocks, nb = id / m_blocks;
   const int m0 = mb * G::BM;
@@ -166,8 +173,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
     for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-  const int n_split = gridDim.y;
-  const int kt0 = (int)((long)nk * blockIdx.y / n_split), kt1 = (int)((long)nk * (blockIdx.y + 1) / n_split);
+  const int kt0 = (int)((long)nk * split / n_split), kt1 = (int)((long)nk * (split + 1) / n_split);
   G::run(acc, op, kt0, kt1, lds);
 
 #ifdef BS_DBG_NOEPI
@@ -203,7 +209,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
             for (int j = 0; j < 4; ++j) v[j] = (f16)acc[mi][ni][4 * i4 + j];
             *(f16x4*)((f16*)out + o) = v;
           } else {
-            *(f32x4*)((float*)out + (size_t)blockIdx.y * M_max * N + o) =
+            *(f32x4*)((float*)out + (size_t)split * M_max * N + o) =
                 f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
           }
         }
@@ -219,9 +225,10 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * 32 : 4 * NT * 32;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
   int total = m_blocks * n_blocks;
-  int grid = ((total + 7) / 8) * 8;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid, n_split), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
-                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks);
+  int xps = 8 / n_split;                                   // n_split is 1, 2, 4 or 8
+  int grid = 8 * ((total + xps - 1) / xps);
+  hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
+                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split);
 }
 
 template <typename T, int EPI>
@@ -274,6 +281,7 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
     if (n_split > 4 && !env_split) n_split = 4;
     if (n_split > kMaxGemmSplit) n_split = kMaxGemmSplit;
     if (n_split > nk) n_split = nk;
+    n_split = n_split >= 8 ? 8 : n_split >= 4 ? 4 : n_split >= 2 ? 2 : 1;      // a split owns 8/S whole XCDs
   }
 #define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
   if constexpr (EPI != EPI_SWIGLU) {
