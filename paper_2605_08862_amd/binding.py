@@ -7,7 +7,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("BS_LIB", os.path.join(_HERE, "libbubblespec.so"))   # BS_LIB: alternative build (debugging)
+LIB_PATH = os.path.join(_HERE, "libbubblespec.so")
 
 BS_OK, BS_EINVAL, BS_ESHAPE, BS_ECAPACITY, BS_ESTATE, BS_EHIP = range(6)
 BS_F32, BS_BF16 = 0, 1

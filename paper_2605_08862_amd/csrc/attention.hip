@@ -3,14 +3,18 @@
 // sequence b attends to cache positions 0 .. c_b + i.
 //
 // MI355X design (bf16 models).  The kernel is HBM-bound: it must stream the committed K/V once.
-//   * A workgroup owns (sequence, KV head, KV split).  All (k_b+1)*G query rows that share the KV
-//     head are packed into 32-row MFMA tiles, so K/V are read once for all of them (the paper's
-//     point: the extra draft rows ride in the matrix tile for free).
+//   * A workgroup owns (sequence, KV head, KV split, query block).  All (k_b+1)*G query rows that
+//     share the KV head are packed into 32-row MFMA tiles, so K/V are read from HBM once for all of
+//     them (the paper's point: the extra draft rows ride in the matrix tile for free).  When there
+//     are too few (sequence, KV head) units for 256 CUs, the query tiles of a unit go to different
+//     workgroups placed on one XCD (shared L2) rather than splitting the token range: no partial
+//     results, no merge kernel (measured, batch 64 x 2 KV heads, context 2048: 31 us against 35 us +
+//     a 6.6 us merge kernel for the two-way token split).
 //   * The 4 waves of a workgroup take different 32-token tiles; each keeps its own online-softmax
 //     state (running max m, sum l) and output accumulator and they are merged once at the end.
 //   * K/V pages are stored in MFMA operand order (see common.h), so a wave's 16-byte-per-lane
 //     load is one contiguous 1 KiB read that lands directly in the operand registers: no LDS
-//     staging, no bank conflicts, no shuffles.  LDS is used only for the final cross-wave merge.
+//     staging, no bank conflicts, no shuffles.  LDS holds the query fragments and, at the end, the cross-wave merge.
 //   * Arithmetic runs on the f16 MFMA: queries and probabilities carry 11 significant bits (with
 //     8-bit bf16 queries the logits of the 7B-shape slice drift by 3e-2).  The cache holds
 //     bf16-rounded K/V values in float16 encoding, so page data are MFMA operands as they are.
@@ -21,6 +25,7 @@
 #include "attn_simple.h"
 #include "gemm_mfma.h"
 #include <stdlib.h>
+#include <type_traits>
 
 namespace {
 constexpr int kMaxSplit = 16;
@@ -35,31 +40,40 @@ __device__ __forceinline__ f16x8 pack_f16x8(const float* v) {
 
 // NQ: query-row tiles (of 32) handled by one wave; QG: groups of waves, each group owning NQ of the
 // workgroup's NQ*QG query tiles (tokens are split across the 4/QG waves of a group).
-// Partial layout (n_split > 1): part_ml [B][Hkv][n_split][RP][2], part_o [B][Hkv][n_split][RP][D],
-// RP = 32*NQ*QG.
+// A (sequence, KV head) unit is covered by n_split * q_blocks workgroups: KV split `split` of the token
+// range times query block `qb` (NQ*QG query tiles each).  Workgroups of different query blocks stream the
+// same K/V; the one-dimensional grid is decoded so that all workgroups of a unit run on the same XCD
+// (ids are dealt round-robin to the 8 XCDs) and are dispatched back to back, so the second reader hits
+// that XCD's L2 and HBM is still read once.
+// Partial layout (n_split > 1): part_ml [units][n_split][RPT][2], part_o [units][n_split][RPT][D], RPT =
+// 32 * (query tiles of a unit).
 template <int NQ, int QG, int D>
-__global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int Hq, int Hkv, float scale_log2e,
+__global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B, int Hq, int Hkv, float scale_log2e,
                                                         const f16* __restrict__ q, const f16* __restrict__ k_pages,
                                                         const f16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
-                                                        int n_split) {
+                                                        int n_split, int q_blocks) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product
   constexpr int DT = D / 32;            // 32-wide d tiles of the output
   constexpr int RP = 32 * NQ * QG;      // padded query rows per workgroup
   constexpr int WPG = 4 / QG;           // waves per group (token split inside the workgroup)
-  constexpr int SLOT = NQ * DT * 16 * 64;               // floats of one wave's output accumulator
+  constexpr int ROWS_W = 32 * NQ;       // query rows held by one wave
+  constexpr int LDO = D + 4;            // row stride (floats) of an accumulator in LDS: 4 banks of skew per row
   extern __shared__ __align__(16) char lds_raw[];
-  float* s_o = (float*)lds_raw;                         // [2 slots][SLOT] accumulators in flight during the merge
-  float* s_m = s_o + 2 * SLOT;                          // [4][32*NQ] per-wave running max
-  float* s_l = s_m + 4 * 32 * NQ;                       // [4][32*NQ] per-wave sum
 
-  const int h = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
+  const int zdim = n_split * q_blocks;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int z = slot % zdim, unit = (slot / zdim) * 8 + xcd;
+  if (unit >= B * Hkv) return;
+  const int h = unit % Hkv, b = unit / Hkv, split = z % n_split;
+  const int qt0 = (z / n_split) * NQ * QG;              // first query tile of this workgroup
   const int k = p.seq_k[b];
   if (k < 0) return;
   const int G = Hq / Hkv;
   const int c = p.seq_c[b];
   const int n_tok = c + k + 1;
   const int R = (k + 1) * G;
+  if (qt0 * 32 >= R) return;                            // this sequence has fewer query rows
   // the wave index is made scalar so that everything derived from it (tile index, block-table lookups)
   // stays on the scalar unit: a vector load of a page id inside the loop would force vmcnt(0) and
   // serialise the K/V prefetch
@@ -73,42 +87,65 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
   // Query fragments (B operand: lane (n, g) holds Q[row n][g*D/2 + 8s + j]) are staged once in LDS in
   // fragment order and re-read per use: keeping them in registers would push the kernel into spills,
   // and a spill reload inside the loop forces vmcnt(0), i.e. it serialises the K/V prefetch.
-  u32x4* s_q = (u32x4*)lds_raw;                         // [RP/32][KS][64] (aliases s_o; dead before the merge)
+  u32x4* s_q = (u32x4*)lds_raw;                         // [RP/32][KS][64] (the region is reused by the merge)
   int lim[NQ];                                          // last visible cache position of the lane's row
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
-    const int qr = (grp * NQ + qt) * 32 + ln;
+    const int qr = (qt0 + grp * NQ + qt) * 32 + ln;
     lim[qt] = (qr < R) ? c + qr / G : -1;
   }
   const int n_tiles = (n_tok + kTile - 1) / kTile;
   const int tps = (n_tiles + n_split - 1) / n_split;
   const int t_begin = split * tps, t_end = min(t_begin + tps, n_tiles);
-  const bool group_active = (grp * NQ * 32) < R;        // wave-uniform
-  auto load_tile = [&](int t, u32x4 (&kf)[KS], u32x4 (&vf)[DT * 2]) {
+  const bool group_active = ((qt0 + grp * NQ) * 32) < R;        // wave-uniform
+  // tiles of this wave: t0, t0 + WPG, ... (n_my of them)
+  const int t0 = t_begin + wig;
+  const int n_my = (group_active && t0 < t_end) ? (t_end - t0 + WPG - 1) / WPG : 0;
+  const int t_last = t0 + (n_my - 1) * WPG;
+  auto tile_offset = [&](int t) -> size_t {
     const int tb = t * kTile;
     const int page = min(max(bt[tb / kPage], 0), kv.n_pages - 1);
-    const size_t off = (size_t)page * page_elems + (size_t)(h * 2 + ((tb / kTile) & 1)) * (kTile * D) + lane * 8;
+    return (size_t)page * page_elems + (size_t)(h * 2 + ((tb / kTile) & 1)) * (kTile * D) + lane * 8;
+  };
+  auto load_k = [&](size_t off, u32x4 (&kf)[KS]) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) kf[s] = *(const u32x4*)(k_pages + off + s * 512);
+  };
+  auto load_v = [&](size_t off, u32x4 (&vf)[DT * 2]) {
 #pragma unroll
     for (int x = 0; x < DT * 2; ++x) vf[x] = *(const u32x4*)(v_pages + off + x * 512);
   };
-  // register double buffering; the first tile is requested before the queries are staged so that its
-  // latency overlaps that work
-  u32x4 ka[KS], va[DT * 2], kb[KS], vb[DT * 2];
-  int t = t_begin + wig;
-  if (group_active && t < t_end) load_tile(t, ka, va);
 
-  for (int f = wave; f < (RP / 32) * KS; f += 4) {      // one fragment (1 KiB) per wave iteration
+  // Prologue order: the query fragments are requested first and the first two K/V tiles right behind
+  // them, so that staging the queries in LDS only waits for the (older) query loads while 32 KiB of
+  // K/V per wave are already in flight.
+  constexpr int QF = (RP / 32) * KS / 4;                // query fragments (1 KiB) staged by each wave
+  u32x4 qv[QF];
+#pragma unroll
+  for (int j = 0; j < QF; ++j) {
+    const int f = wave + 4 * j;
     const int qtile = f / KS, s = f % KS;
-    const int qr = qtile * 32 + ln;
-    u32x4 v = u32x4{0, 0, 0, 0};
-    if (qr < R) {
-      const int iq = qr / G, hg = qr % G;
-      v = *(const u32x4*)(q + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + lg * (D / 2) + s * 8);
-    }
-    s_q[f * 64 + lane] = v;
+    const int qr = min((qt0 + qtile) * 32 + ln, R - 1);         // clamped rows are never used: their scores are masked
+    const int iq = qr / G, hg = qr % G;
+    qv[j] = *(const u32x4*)(q + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D + lg * (D / 2) + s * 8);
   }
+  // Two K/V tiles live in registers (k0/v0, k1/v1).  A buffer is refilled with the tile two steps
+  // ahead as soon as its MFMAs have been issued: K right after the score product, V right after the
+  // output product, so between 16 and 32 KiB per wave are in flight at any time and no register
+  // copies are needed.  All refills are unconditional (clamped to the wave's last tile).
+  u32x4 k0[KS], v0[DT * 2], k1[KS], v1[DT * 2];
+  {
+    // unconditional (a wave without tiles reads the sequence's last tile and ignores it): loads issued under
+    // a branch would make the wait for the query loads above a wait for everything
+    const int ta = min(t0, n_tiles - 1), tb = n_my > 1 ? t0 + WPG : ta;
+    const size_t oa = tile_offset(ta), ob = tile_offset(tb);
+    load_k(oa, k0);
+    load_v(oa, v0);
+    load_k(ob, k1);
+    load_v(ob, v1);
+  }
+#pragma unroll
+  for (int j = 0; j < QF; ++j) s_q[(wave + 4 * j) * 64 + lane] = qv[j];
   __syncthreads();
   const u32x4* my_q = s_q + (size_t)(grp * NQ) * KS * 64 + lane;
 
@@ -124,7 +161,12 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
       for (int i = 0; i < 16; ++i) o[qt][dt][i] = 0.f;
   }
 
-  auto compute_tile = [&](int t, const u32x4 (&kc)[KS], const u32x4 (&vc)[DT * 2]) {
+  // One tile: scores from kc, refill kc with tile t_pref, softmax, output product from vc, refill vc.
+  auto tile = [&](auto pref, int t, int t_pref, u32x4 (&kc)[KS], u32x4 (&vc)[DT * 2]) {
+    constexpr bool PREF = decltype(pref)::value;
+    // the block-table entry of the refill tile is requested (scalar load) before the score product, so
+    // that its latency is over by the time the refill is issued
+    const size_t off_pref = PREF ? tile_offset(t_pref) : 0;
     const int tok0 = t * kTile + 16 * lg;               // accumulator register i <-> token tok0 + i
     const bool full = (t + 1) * kTile - 1 <= c;         // every token visible to every row: no masking
     f32x16 st[NQ];
@@ -139,6 +181,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
       for (int qt = 0; qt < NQ; ++qt)
         st[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, as_f16x8(my_q[(qt * KS + s) * 64]), st[qt], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (PREF) load_k(off_pref, kc);
     __builtin_amdgcn_sched_barrier(0);
     f16x8 pf[NQ][2];
 #pragma unroll
@@ -185,120 +229,93 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int H
         for (int qt = 0; qt < NQ; ++qt)
           o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, pf[qt][t2], o[qt][dt], 0, 0, 0);
       }
+    __builtin_amdgcn_sched_barrier(0);
+    if (PREF) load_v(off_pref, vc);
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  if (group_active) {
-    for (; t < t_end; t += WPG) {
-      // current tile -> kb/vb (register moves), next tile requested into ka/va, then compute: the
-      // loads of tile t+WPG are in flight during the whole computation of tile t
-#pragma unroll
-      for (int s = 0; s < KS; ++s) kb[s] = ka[s];
-#pragma unroll
-      for (int x = 0; x < DT * 2; ++x) vb[x] = va[x];
-      load_tile(t + WPG < t_end ? t + WPG : t, ka, va);   // unconditional (the last one re-reads tile t): a
-      compute_tile(t, kb, vb);                             // conditional prefetch costs vmcnt(0) waits
+  {
+    int i = 0;
+    for (; i + 2 <= n_my; i += 2) {
+      const int t = t0 + i * WPG;
+      tile(std::true_type{}, t, min(t + 2 * WPG, t_last), k0, v0);
+      tile(std::true_type{}, t + WPG, min(t + 3 * WPG, t_last), k1, v1);
     }
+    if (i < n_my) tile(std::false_type{}, t0 + i * WPG, 0, k0, v0);
   }
-  __syncthreads();                                      // all waves are done with s_q before s_o reuses it
+  __syncthreads();                                      // all waves are done with the query fragments
 
-  // ---- merge the waves of each group (tree, accumulators cross LDS in register order) --------
+  // ---- merge the waves of each group -----------------------------------------------------------
+  // Every wave stores its unscaled accumulator (rows x D, row-major, padded rows) and its per-row
+  // (max, sum) in LDS; after ONE barrier all 256 threads combine them: TPR threads per query row, each
+  // sums its 16-byte chunks over the waves of the row's group with the usual exp2(m_w - m) weights and
+  // writes the result (final rows: normalised float16; KV splits: float32 partial + (m, l)).
+  float* s_o = (float*)lds_raw;                         // [4 waves][ROWS_W][LDO]
+  float* s_m = s_o + 4 * ROWS_W * LDO;                  // [4][ROWS_W] per-wave running max
+  float* s_l = s_m + 4 * ROWS_W;                        // [4][ROWS_W] per-wave sum
+  {
+    float* mine = s_o + (size_t)wave * ROWS_W * LDO;
 #pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    l_run[qt] += __shfl_xor(l_run[qt], 32);
-    if (lg == 0) {
-      s_m[wave * 32 * NQ + qt * 32 + ln] = m_run[qt];
-      s_l[wave * 32 * NQ + qt * 32 + ln] = l_run[qt];
-    }
-  }
-  __syncthreads();
-  float m_tot[NQ], l_tot[NQ];
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    float mt = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < WPG; ++w) mt = fmaxf(mt, s_m[(grp * WPG + w) * 32 * NQ + qt * 32 + ln]);
-    const float ms = (mt == -INFINITY) ? 0.f : mt;
-    float lt = 0.f;
-#pragma unroll
-    for (int w = 0; w < WPG; ++w) {
-      const int o2 = (grp * WPG + w) * 32 * NQ + qt * 32 + ln;
-      lt += s_l[o2] * exp2f(s_m[o2] - ms);
-    }
-    m_tot[qt] = mt;
-    l_tot[qt] = lt;
-    const float f_own = exp2f(m_run[qt] - ms);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[qt][dt][i] *= f_own;
-  }
-  // slot of a group: QG == 1 uses both slots in the first round, QG == 2 one slot per group
-  auto put = [&](float* slot) {
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt)
+    for (int qt = 0; qt < NQ; ++qt) {
+      l_run[qt] += __shfl_xor(l_run[qt], 32);
+      if (lg == 0) {
+        s_m[wave * ROWS_W + qt * 32 + ln] = m_run[qt];
+        s_l[wave * ROWS_W + qt * 32 + ln] = l_run[qt];
+      }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4)
-          *(f32x4*)(slot + (((qt * DT + dt) * 4 + i4) * 64 + lane) * 4) =
+          *(f32x4*)(mine + (qt * 32 + ln) * LDO + dt * 32 + 8 * i4 + 4 * lg) =
               f32x4{o[qt][dt][4 * i4], o[qt][dt][4 * i4 + 1], o[qt][dt][4 * i4 + 2], o[qt][dt][4 * i4 + 3]};
-  };
-  auto add = [&](const float* slot) {
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 v = *(const f32x4*)(slot + (((qt * DT + dt) * 4 + i4) * 64 + lane) * 4);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) o[qt][dt][4 * i4 + j] += v[j];
-        }
-  };
-  if (WPG == 4) {
-    if (wig >= 2) put(s_o + (wig - 2) * SLOT);
-    __syncthreads();
-    if (wig < 2) add(s_o + wig * SLOT);
-    __syncthreads();
-    if (wig == 1) put(s_o);
-    __syncthreads();
-    if (wig == 0) add(s_o);
-  } else {
-    if (wig == 1) put(s_o + grp * SLOT);
-    __syncthreads();
-    if (wig == 0) add(s_o + grp * SLOT);
+    }
   }
-
-  // ---- write from registers (first wave of each group): final rows or split partials -------------
-  if (wig == 0) {
+  __syncthreads();
+  {
+    constexpr int TPR = 256 / RP;                       // threads per query row
+    constexpr int CH = D / 4;                           // 16-byte chunks per row
+    const int wr = threadIdx.x / TPR, sub = threadIdx.x % TPR;
+    const int g = wr / ROWS_W, lr = wr % ROWS_W;
+    const int qr = qt0 * 32 + wr;
+    if (qr < R) {
+      float mw[WPG], mt = -INFINITY;
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      const int qr = (grp * NQ + qt) * 32 + ln;
-      if (qr >= R) continue;
-      const int iq = qr / G, hg = qr % G;
-      if (n_split == 1) {
-        const float inv = 1.0f / l_tot[qt];
-        f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
-            typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-            f16x4 v;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (f16)(o[qt][dt][4 * i4 + j] * inv);
-            *(f16x4*)(dst + dt * 32 + 8 * i4 + 4 * lg) = v;
-          }
-      } else {
-        const size_t pr = (((size_t)b * Hkv + h) * n_split + split) * RP + qr;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4)
-            *(f32x4*)(part_o + pr * D + dt * 32 + 8 * i4 + 4 * lg) =
-                f32x4{o[qt][dt][4 * i4], o[qt][dt][4 * i4 + 1], o[qt][dt][4 * i4 + 2], o[qt][dt][4 * i4 + 3]};
-        if (lg == 0) { part_ml[pr * 2] = m_tot[qt]; part_ml[pr * 2 + 1] = l_tot[qt]; }
+      for (int w = 0; w < WPG; ++w) {
+        mw[w] = s_m[(g * WPG + w) * ROWS_W + lr];
+        mt = fmaxf(mt, mw[w]);
       }
+      const float ms = (mt == -INFINITY) ? 0.f : mt;
+      float lt = 0.f;
+#pragma unroll
+      for (int w = 0; w < WPG; ++w) {
+        mw[w] = __builtin_amdgcn_exp2f(mw[w] - ms);      // weight of wave w (0 for a wave that saw no token)
+        lt += s_l[(g * WPG + w) * ROWS_W + lr] * mw[w];
+      }
+      const int iq = qr / G, hg = qr % G;
+      const float inv = 1.0f / lt;                      // row i always sees at least position c + i: lt > 0
+      f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
+      const size_t pr = ((size_t)unit * n_split + split) * ((size_t)RP * q_blocks) + qr;
+#pragma unroll
+      for (int j = 0; j < CH / TPR; ++j) {
+        const int ch = sub + j * TPR;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < WPG; ++w) {
+          const f32x4 v = *(const f32x4*)(s_o + ((size_t)(g * WPG + w) * ROWS_W + lr) * LDO + ch * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[e] += v[e] * mw[w];
+        }
+        if (n_split == 1) {
+          typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+          f16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (f16)(acc[e] * inv);
+          *(f16x4*)(dst + ch * 4) = v;
+        } else {
+          *(f32x4*)(part_o + pr * D + ch * 4) = acc;
+        }
+      }
+      if (n_split > 1 && sub == 0) { part_ml[pr * 2] = mt; part_ml[pr * 2 + 1] = lt; }
     }
   }
 }
@@ -313,7 +330,7 @@ __global__ void __launch_bounds__(D) attn_merge_kernel(Plan p, int Hq, int Hkv, 
   const int b = p.row_seq[r], iq = p.row_pos[r];
   const int G = Hq / Hkv, h = hq / G, hg = hq % G;
   const int qr = iq * G + hg;
-  const size_t base = (((size_t)b * Hkv + h) * n_split) * RP + qr;
+  const size_t base = (((size_t)b * Hkv + h) * n_split) * RP + qr;   // RP: padded query rows of a unit
   float mt = -INFINITY;
   for (int s = 0; s < n_split; ++s) mt = fmaxf(mt, part_ml[(base + (size_t)s * RP) * 2]);
   float lt = 0.f, acc = 0.f;
@@ -344,21 +361,26 @@ size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max) {
 template <int NQ, int QG, int D>
 static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int B, int M_max, const void* q,
                              const void* k_pages, const void* v_pages, void* out, void* scratch, int n_split,
-                             void* prof_token, hipStream_t st) {
+                             int q_blocks, void* prof_token, hipStream_t st) {
   constexpr int RP = 32 * NQ * QG;
-  const size_t lds = (size_t)2 * NQ * (D / 32) * 16 * 64 * 4 + 2 * 4 * 32 * NQ * 4;   // two accumulator slots + statistics (>= the query fragments)
+  const int rpt = RP * q_blocks;                                       // padded query rows of a unit
+  size_t lds = (size_t)4 * 32 * NQ * (D + 4) * 4 + 2 * 4 * 32 * NQ * 4;   // accumulators of 4 waves + statistics
+  const size_t lds_q = (size_t)(RP / 32) * (D / 16) * 1024;           // query fragments (same region, earlier)
+  if (lds < lds_q) lds = lds_q;
   float* part_ml = (float*)scratch;
-  float* part_o = part_ml + (size_t)B * s.Hkv * n_split * RP * 2;
+  float* part_o = part_ml + (size_t)B * s.Hkv * n_split * rpt * 2;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   auto kern = attn_mfma_kernel<NQ, QG, D>;
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
+  const int units = B * s.Hkv;
+  const int grid = (units + 7) / 8 * 8 * n_split * q_blocks;
   if (prof_token) attention_prof_mark(prof_token, st, true);
-  hipLaunchKernelGGL(kern, dim3(s.Hkv, B, n_split), dim3(256), lds, st, p, kv, s.Hq, s.Hkv, scale_log2e,
-                     (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, n_split);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p, kv, B, s.Hq, s.Hkv, scale_log2e, (const f16*)q,
+                     (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, n_split, q_blocks);
   if (prof_token) attention_prof_mark(prof_token, st, false);
   if (n_split > 1)
-    hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, RP, part_o, part_ml,
+    hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, rpt, part_o, part_ml,
                        n_split, (f16*)out);
 }
 
@@ -377,17 +399,30 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
                        (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out);
     return;
   }
-  static const char* split_env = getenv("BS_ATTN_SPLIT");
-  int n_split = split_env ? atoi(split_env) : (256 + B * s.Hkv / 2) / (B * s.Hkv);   // ~ one workgroup per CU
+  // Shape of the launch.  A unit = (sequence, KV head) has `tiles` query tiles of 32 rows.  With enough
+  // units to fill the 256 CUs one workgroup takes all tiles of a unit (K/V fragments are loaded once and
+  // used for every tile); with fewer units the query tiles are spread over q_blocks workgroups (the extra
+  // readers hit L2), and what is still missing to reach ~256 workgroups comes from splitting the token
+  // range (n_split, which costs a merge kernel).
+  static const char* split_env = getenv("BS_ATTN_SPLIT");          // tuning aids
+  static const char* qb_env = getenv("BS_ATTN_QBLOCKS");
+  const int tiles = rows_padded(s, k_max) / 32;                    // 1, 2 or 4
+  const int units = B * s.Hkv;
+  int q_blocks = 1;
+  if (tiles == 2 && units < 256) q_blocks = 2;
+  if (tiles == 4) q_blocks = units < 128 ? 4 : (units < 256 ? 2 : 1);
+  if (qb_env) { const int v = atoi(qb_env); if (v >= 1 && v <= tiles && tiles % v == 0) q_blocks = v; }
+  const int wgs = units * q_blocks;
+  int n_split = split_env ? atoi(split_env) : (256 + wgs / 2) / wgs;   // ~ one workgroup per CU
   n_split = n_split < 1 ? 1 : (n_split > kMaxSplit ? kMaxSplit : n_split);
-  const int tiles = (rows_padded(s, k_max)) / 32;
+  const int tiles_wg = tiles / q_blocks;                           // query tiles per workgroup: 1, 2 or 4
 #define BS_ATTN(NQ, QG)                                                                                         \
   do {                                                                                                          \
-    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, prof_token, st); \
-    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, prof_token, st);   \
+    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, q_blocks, prof_token, st); \
+    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, q_blocks, prof_token, st);   \
   } while (0)
-  if (tiles == 1) BS_ATTN(1, 1);
-  else if (tiles == 2) BS_ATTN(2, 1);
+  if (tiles_wg == 1) BS_ATTN(1, 1);
+  else if (tiles_wg == 2) BS_ATTN(2, 1);
   else BS_ATTN(2, 2);
 #undef BS_ATTN
 }

@@ -114,7 +114,8 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 // 8/S XCDs, and inside a split each XCD takes a contiguous range of (N block, M block) tiles, M block
 // fastest.  The M blocks that share a weight tile then run back to back on one XCD and hit its L2, and
 // an XCD only ever touches its own K range of the activation matrix (measured before this mapping: the
-// down projection fetched 122 MB per launch for 38 MB of operands, every L2 pulling the whole matrix).  The float32 epilogues (QKV projection, residual projections) write one partial
+// down projection fetched 122 MB per launch for 38 MB of operands, every L2 pulling the whole matrix).
+// The float32 epilogues (QKV projection, residual projections) write one partial
 // [M_max, N] slab per K split, out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums
 // the slabs.  Float atomics into the residual were measured at ~25 us per launch and are not used.
 template <int MT, int NT, int EPI>
@@ -138,9 +139,6 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   const int mb = id % m_blocks, nb = id / m_blocks;
   const int m0 = mb * G::BM;
   if (m0 >= M) return;
-#ifdef BS_DBG_EXIT0
-  return;
-#endif
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   static_assert(!GLU || NT == 2, "SwiGLU pairs one gate tile with one up tile per wave");
   constexpr int NOUT_W = GLU ? 32 : NT * 32;            // output columns per wave
@@ -176,9 +174,6 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   const int kt0 = (int)((long)nk * split / n_split), kt1 = (int)((long)nk * (split + 1) / n_split);
   G::run(acc, op, kt0, kt1, lds);
 
-#ifdef BS_DBG_NOEPI
-  if (acc[0][0][0] != 12345.678f) return;
-#endif
   typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
 #pragma unroll

@@ -88,9 +88,6 @@ struct MfmaGemm {
     for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-#ifdef BS_DBG_NOW
-        if (kt > 0) continue;
-#endif
         wreg[STAGE][ni][s] = *(const u32x4*)(op.w_tiles[ni] + (size_t)kt * kWBlock + s * 512);
       }
   }
