@@ -110,7 +110,8 @@ size_t bs_workspace_bytes(const bs_model_desc* desc, int B_max, int k_max);
  * matrices into the workspace (float16, matrix-unit operand order); after that work has finished
  * the library no longer reads wqkv / wo / w_gate_up / w_down / lm_head (embed and the norm gains
  * are still read in place).  Errors: BS_EINVAL (null / bad dtype), BS_ESHAPE (unsupported shape: head_dim
- * not in {64,128}, d_model or d_ffn not a multiple of 64, Hq % Hkv != 0, k_max > BS_MAX_K, ...),
+ * not in {64,128}, d_model or d_ffn not a multiple of 64, d_model > 16384, Hq % Hkv != 0,
+ * k_max > BS_MAX_K, bf16 models with (k_max+1) * Hq/Hkv > 128),
  * BS_ECAPACITY (workspace too small). */
 bs_status bs_create(const bs_model_desc* desc, const bs_weights* weights, const bs_kv_desc* kv,
                     void* workspace, size_t workspace_bytes, int B_max, int k_max, void* stream,

@@ -17,6 +17,7 @@ struct bs_ctx {
   // workspace
   Plan plan;
   float* h;            // residual stream  [M_max, d] float32
+  double* inv_freq;    // [D/2] rotary frequencies
   std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down;         // bf16 models: packed copies in the workspace
   void* pk_lm = nullptr;
   void* a;             // normed rows      [M_max, d] (GEMM operand type: float32 / float16)
@@ -64,6 +65,7 @@ size_t elt(int dtype) { return dtype == BS_F32 ? 4 : 2; }
 bs_status check_desc(const bs_model_desc* d, int B_max, int k_max) {
   if (!d) return BS_EINVAL;
   if (d->dtype != BS_F32 && d->dtype != BS_BF16) return BS_EINVAL;
+  if (d->d_model > 16384) return BS_ESHAPE;               // the normalisation kernel keeps a row in registers
   if (d->n_layers < 1 || d->d_model < 64 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 64 || d->vocab < 2)
     return BS_ESHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return BS_ESHAPE;
@@ -93,6 +95,7 @@ size_t carve(bs_ctx* c, char* base) {
   p.row_tok = w.take<int32_t>(M);
   p.row_target = w.take<int32_t>(M);
   c->h = w.take<float>((size_t)M * s.d);
+  c->inv_freq = w.take<double>(64);
   c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
   c->qkv = w.take<float>((size_t)M * s.Nqkv());
   c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
@@ -257,6 +260,7 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   }
   c->final_norm = w->final_norm;
   c->kv = KvView{kv->n_pages, kv->n_slots, kv->max_pages_per_seq, kv->block_table, kv->ctx_len};
+  launch_rope_table(c->s, c->inv_freq, (hipStream_t)stream);
   launch_clear_status(c->plan.status, (hipStream_t)stream);
   st = check_hip(c);
   if (st != BS_OK) { delete c; return st; }
@@ -345,7 +349,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
     { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
       nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
                        slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
-    launch_rope_append(s, p, c->kv, M_max, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
+    launch_rope_append(s, p, c->kv, M_max, c->inv_freq, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
                        c->v_pages[l], st);
     launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);

@@ -107,8 +107,10 @@ void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, f
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
                     const float* gain, void* out, hipStream_t st);
 // qkv is the float32 projection, given as n_slabs >= 1 slabs [M_max, Nqkv] that are summed.
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, int n_slabs,
-                        void* q_out, void* k_pages, void* v_pages, hipStream_t st);
+// inv_freq: [D/2] float64 table written by launch_rope_table.
+void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st);
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const double* inv_freq,
+                        const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
 // gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue.  float32 models: A, W float32 row-major.

@@ -26,89 +26,164 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 // (float32 for float32 models, float16 for bf16 models).
 // With n_slabs > 0 the row first absorbs the K-split slabs of the preceding residual projection:
 // h[r] += sum_s slabs[s][r] (the updated residual is written back).
-template <typename T>
+// One workgroup per row; the row (d <= 1024 * NV floats) stays in registers between the sum of squares
+// and the scaling, so every operand is read once and the kernel has a single barrier.
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct Vec4<f16> { typedef _Float16 type __attribute__((ext_vector_type(4))); };
+
+template <typename T, int NV>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, float* __restrict__ h,
                                                       const float* __restrict__ slabs, int n_slabs, size_t slab_stride,
                                                       const float* __restrict__ gain, T* __restrict__ out) {
   __shared__ float red[4];
-  int r = blockIdx.x;
+  const int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
-  float* x = h + (size_t)r * d;
-  float ss = 0.f;
   typedef float f4 __attribute__((ext_vector_type(4)));
-  if (n_slabs > 0) {                       // d is a multiple of 64: 16-byte accesses throughout
-    const float* sl = slabs + (size_t)r * d;
-    for (int i = threadIdx.x * 4; i < d; i += 1024) {
-      f4 v = *(const f4*)(x + i);
-      for (int s = 0; s < n_slabs; ++s) v += *(const f4*)(sl + (size_t)s * slab_stride + i);
-      *(f4*)(x + i) = v;
-      ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-    }
-  } else {
-    for (int i = threadIdx.x * 4; i < d; i += 1024) {
-      const f4 v = *(const f4*)(x + i);
-      ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  float* x = h + (size_t)r * d;
+  const float* sl = slabs + (size_t)r * d;
+  f4 v[NV], gn[NV];
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int i = (it * 256 + threadIdx.x) * 4;          // d is a multiple of 64: 16-byte accesses throughout
+    v[it] = f4{0.f, 0.f, 0.f, 0.f};
+    gn[it] = v[it];
+    if (i < d) {
+      v[it] = *(const f4*)(x + i);
+      gn[it] = *(const f4*)(gain + i);
     }
   }
-  ss = block_sum_256(ss, red);
-  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int s = 0; s < n_slabs; ++s) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int i = (it * 256 + threadIdx.x) * 4;
+      if (i < d) v[it] += *(const f4*)(sl + (size_t)s * slab_stride + i);
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int i = (it * 256 + threadIdx.x) * 4;
+    if (n_slabs > 0 && i < d) *(f4*)(x + i) = v[it];
+    ss += v[it][0] * v[it][0] + v[it][1] * v[it][1] + v[it][2] * v[it][2] + v[it][3] * v[it][3];
+  }
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = red[0] + red[1] + red[2] + red[3];
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
   T* o = out + (size_t)r * d;
-  for (int i = threadIdx.x; i < d; i += 256) o[i] = from_f32<T>(x[i] * inv * gain[i]);
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int i = (it * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      typename Vec4<T>::type w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = from_f32<T>(v[it][e] * inv * gn[it][e]);
+      *(typename Vec4<T>::type*)(o + i) = w;
+    }
+  }
+}
+
+// Inverse rotary frequencies theta^(-2j/D), j < D/2, in float64 (filled once per context).
+__global__ void rope_table_kernel(int D, float theta, double* __restrict__ inv_freq) {
+  const int j = threadIdx.x;
+  if (j < D / 2) inv_freq[j] = exp2(-2.0 * (double)j / (double)D * log2((double)theta));
 }
 
 // Rotary (pairs (j, j + D/2), angle = position * theta^(-2j/D)) on q and k of packed row r at
-// absolute position c_b + i.  The QKV projection arrives in float32 (so each of q, k, v is rounded
-// exactly once, after the rotation): q goes to the query buffer (float16 for bf16 models: it is an
-// attention operand, not cache data), k and v to the slot's page in the cache dtype.  Angles are formed in float64: at positions
-// of 3e4 a float32 angle is already off by ~2e-3 rad.
+// absolute position c_b + i.  The QKV projection arrives in float32, as n_slabs K-split slabs that are
+// summed here (so each of q, k, v is rounded exactly once, after the rotation): q goes to the query
+// buffer (float16 for bf16 models: it is an attention operand, not cache data), k and v to the slot's
+// page in the cache dtype.
+// Angles are formed in float64 (at positions of 3e4 a float32 angle is already off by ~2e-3 rad), reduced
+// to [-pi, pi] in float64 and only then handed to the float32 sine / cosine.
+// One workgroup per row; a work item is four consecutive rotation pairs of one head (two 16-byte loads
+// per slab, 8-byte stores) or four consecutive v elements.
 template <typename T, typename TQ, typename TP>
-__global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D, float theta,
+__global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D,
+                                                          const double* __restrict__ inv_freq,
                                                           const float* __restrict__ qkv, int n_slabs, size_t slab_stride,
                                                           TQ* __restrict__ q_out, TP* __restrict__ k_pages,
                                                           TP* __restrict__ v_pages) {
   __shared__ float s_cos[64], s_sin[64];
-  int r = blockIdx.x;
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
   const int b = p.row_seq[r];
   const int pos = p.seq_c[b] + p.row_pos[r];
-  const int half = D / 2;
+  const int half = D / 2, groups = half / 4;
+  const float* row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
+  const int n_rot = (Hq + Hkv) * groups, n_items = n_rot + Hkv * D / 4;
+  // first item of this thread: loads are issued before the angle computation and the barrier
+  const int idx0 = threadIdx.x;
+  f4 a0 = f4{0.f, 0.f, 0.f, 0.f}, b0 = a0;
+  int hh0 = 0, j0 = 0;
+  if (idx0 < n_rot) {
+    hh0 = idx0 / groups; j0 = (idx0 % groups) * 4;
+    const float* x = row + (size_t)hh0 * D + j0;
+    for (int sl = 0; sl < n_slabs; ++sl) { a0 += *(const f4*)(x + sl * slab_stride); b0 += *(const f4*)(x + sl * slab_stride + half); }
+  }
   if (threadIdx.x < half) {
-    double inv = exp2(-2.0 * (double)threadIdx.x / (double)D * log2((double)theta));
-    double sn, cs;
-    sincos((double)pos * inv, &sn, &cs);
-    s_cos[threadIdx.x] = (float)cs;
-    s_sin[threadIdx.x] = (float)sn;
+    const double ang = (double)pos * inv_freq[threadIdx.x];
+    const double two_pi_hi = 6.283185307179586, two_pi_lo = 2.4492935982947064e-16;
+    const double n = rint(ang * 0.15915494309189535);
+    const double red = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
+    float sn, cs;
+    sincosf((float)red, &sn, &cs);
+    s_cos[threadIdx.x] = cs;
+    s_sin[threadIdx.x] = sn;
   }
   __syncthreads();
-  const float* row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
   TQ* qrow = q_out + (size_t)r * Hq * D;
   const int page = kv.block_table[(size_t)p.seq_slot[b] * kv.max_pages + pos / kPage];
   const int tok = pos % kPage;
   const size_t pbase = (size_t)page * kv_page_elems(Hkv, D);
-  // q heads and k heads: one thread per (head, pair)
-  for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += blockDim.x) {
-    int hh = idx / half, j = idx % half;
-    const float* x = row + (size_t)hh * D;
-    float x1 = x[j], x2 = x[j + half];
-    for (int sl = 1; sl < n_slabs; ++sl) { x1 += x[sl * slab_stride + j]; x2 += x[sl * slab_stride + j + half]; }
-    float c = s_cos[j], s = s_sin[j];
-    float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
-    if (hh < Hq) {
-      qrow[hh * D + j] = from_f32<TQ>(y1);
-      qrow[hh * D + j + half] = from_f32<TQ>(y2);
+  for (int idx = idx0; idx < n_items; idx += 256) {
+    if (idx < n_rot) {
+      int hh = hh0, j = j0;
+      f4 x1 = a0, x2 = b0;
+      if (idx != idx0) {
+        hh = idx / groups; j = (idx % groups) * 4;
+        const float* x = row + (size_t)hh * D + j;
+        x1 = f4{0.f, 0.f, 0.f, 0.f}; x2 = x1;
+        for (int sl = 0; sl < n_slabs; ++sl) { x1 += *(const f4*)(x + sl * slab_stride); x2 += *(const f4*)(x + sl * slab_stride + half); }
+      }
+      float y1[4], y2[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float c = s_cos[j + e], sn = s_sin[j + e];
+        y1[e] = x1[e] * c - x2[e] * sn;
+        y2[e] = x2[e] * c + x1[e] * sn;
+      }
+      if (hh < Hq) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          qrow[hh * D + j + e] = from_f32<TQ>(y1[e]);
+          qrow[hh * D + j + half + e] = from_f32<TQ>(y2[e]);
+        }
+      } else {
+        const int kh = hh - Hq;
+        // rounded to the cache dtype T, stored in the page encoding TP (four consecutive d are contiguous in
+        // both page layouts)
+        TP* k1 = k_pages + pbase + k_index<TP>(D, kh, tok, j);
+        TP* k2 = k_pages + pbase + k_index<TP>(D, kh, tok, j + half);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          k1[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y1[e])));
+          k2[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y2[e])));
+        }
+      }
     } else {
-      int kh = hh - Hq;
-      // rounded to the cache dtype T, stored in the page encoding TP
-      k_pages[pbase + k_index<TP>(D, kh, tok, j)] = from_f32<TP>(to_f32<T>(from_f32<T>(y1)));
-      k_pages[pbase + k_index<TP>(D, kh, tok, j + half)] = from_f32<TP>(to_f32<T>(from_f32<T>(y2)));
+      const int e0 = (idx - n_rot) * 4;                  // four consecutive v elements of one head
+      const int kh = e0 / D, dd = e0 % D;
+      const float* x = row + (size_t)(Hq + Hkv) * D + e0;
+      f4 v = f4{0.f, 0.f, 0.f, 0.f};
+      for (int sl = 0; sl < n_slabs; ++sl) v += *(const f4*)(x + sl * slab_stride);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v_pages[pbase + v_index<TP>(D, kh, tok, dd + e)] = from_f32<TP>(to_f32<T>(from_f32<T>(v[e])));
     }
-  }
-  const float* vrow = row + (size_t)(Hq + Hkv) * D;
-  for (int idx = threadIdx.x; idx < Hkv * D; idx += blockDim.x) {
-    int kh = idx / D, dd = idx % D;
-    float v = vrow[idx];
-    for (int sl = 1; sl < n_slabs; ++sl) v += vrow[sl * slab_stride + idx];
-    v_pages[pbase + v_index<TP>(D, kh, tok, dd)] = from_f32<TP>(to_f32<T>(from_f32<T>(v)));
   }
 }
 
@@ -142,19 +217,22 @@ void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, f
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
                     const float* gain, void* out, hipStream_t st) {
   const size_t stride = (size_t)M_max * s.d;
-  if (s.dtype == BS_F32)
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (float*)out);
-  else
-    hipLaunchKernelGGL(rmsnorm_kernel<f16>, dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (f16*)out);
+#define BS_RMS(T_, NV_) hipLaunchKernelGGL((rmsnorm_kernel<T_, NV_>), dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (T_*)out)
+  if (s.dtype == BS_F32) { if (s.d <= 2048) BS_RMS(float, 2); else if (s.d <= 4096) BS_RMS(float, 4); else BS_RMS(float, 16); }
+  else                   { if (s.d <= 2048) BS_RMS(f16, 2);   else if (s.d <= 4096) BS_RMS(f16, 4);   else BS_RMS(f16, 16); }
+#undef BS_RMS
 }
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* qkv, int n_slabs,
-                        void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
+void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st) {
+  hipLaunchKernelGGL(rope_table_kernel, dim3(1), dim3(64), 0, st, s.D, s.theta, inv_freq);
+}
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const double* inv_freq,
+                        const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
   const size_t stride = (size_t)M_max * s.Nqkv();
   if (s.dtype == BS_F32)
-    hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+    hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, inv_freq,
                        qkv, n_slabs, stride, (float*)q_out, (float*)k_pages, (float*)v_pages);
   else
-    hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, s.theta,
+    hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, inv_freq,
                        qkv, n_slabs, stride, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
