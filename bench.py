@@ -29,7 +29,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 AGREEMENT_NOISE = 0.771          # s with 2*Phi(-s/2) = 0.7 (lognormal closed form for E min(p, q))
 # HBM bytes per launch of each kernel class at the DEFAULT workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a plain copy of known size; see profiles/bench_s1p5b_b64_c2048_k8_kernels.txt).  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {"gemm_gate_up": 69.4e6 + 10.3e6, "gemm_down": 121.7e6 + 14.2e6, "attention": 138.5e6 + 7.2e6}
+MEASURED_TRAFFIC_BYTES = {"gemm_gate_up": 70.1e6 + 12.0e6, "gemm_down": 48.3e6 + 14.2e6, "attention": 138.0e6 + 1.6e6,
+                          "lmhead": 601.3e6 + 36.5e6}
 
 
 def build_workload(args):
@@ -209,7 +210,13 @@ def measure_roofline(wl, args):
         ms, n = B.bs_profile_end(eng.ctx)
         if n:
             per_class[name] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps,
-                                   us_per_launch=1e3 * ms / n)
+                                   us_per_launch_events=1e3 * ms / n)
+    # An event pair adds a fixed cost to what it brackets; the "empty" class (a pair with nothing in between,
+    # once per layer, on the same stream in the same step) measures it, and it is subtracted from every class.
+    overhead_us = per_class.pop("empty")["us_per_launch_events"] if "empty" in per_class else 0.0
+    for c in per_class.values():
+        c["us_per_launch"] = max(c["us_per_launch_events"] - overhead_us, 1e-3)
+        c["ms_per_step"] = c["us_per_launch"] * c["launches_per_step"] * 1e-3
     dom = max((c for c in per_class if c in algo), key=lambda c: per_class[c]["ms_per_step"])
     bound, units = algo[dom]
     sec = per_class[dom]["us_per_launch"] * 1e-6
@@ -226,7 +233,8 @@ def measure_roofline(wl, args):
     traffic = MEASURED_TRAFFIC_BYTES.get(dom) if default_wl else None
     return {"roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                          "frac": achieved / peak, "traffic": traffic,
-                         "us_per_launch": per_class[dom]["us_per_launch"]},
+                         "us_per_launch": per_class[dom]["us_per_launch"],
+                         "event_pair_overhead_us": overhead_us},
             "kernel_classes": per_class}
 
 

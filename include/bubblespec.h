@@ -215,7 +215,9 @@ enum {
   BS_PROF_GEMM_DOWN = 5,
   BS_PROF_LMHEAD = 6,      /* LM-head GEMM with the softmax-statistics epilogue */
   BS_PROF_SAMPLE = 7,      /* residual / bonus inverse-CDF sampling */
-  BS_PROF_LOOKUP = 8       /* draft lookup */
+  BS_PROF_LOOKUP = 8,      /* draft lookup */
+  BS_PROF_EMPTY = 9        /* no kernel: one empty event pair per decoder layer of bs_verify_step, which measures
+                              the fixed cost an event pair adds to every duration reported above */
 };
 bs_status bs_profile_begin(bs_ctx* ctx, int kernel_class);
 bs_status bs_profile_end(bs_ctx* ctx, void* stream, float* total_ms /*host*/, int* launches /*host*/);

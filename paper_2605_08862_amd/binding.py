@@ -20,7 +20,7 @@ EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
            "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end"]
 PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
-                "sample": 7, "lookup": 8}
+                "sample": 7, "lookup": 8, "empty": 9}
 
 
 class bs_model_desc(C.Structure):
@@ -201,3 +201,11 @@ def bs_profile_end(ctx):
     ms, n = C.c_float(0), C.c_int(0)
     _check(ctx, lib().bs_profile_end(ctx, _stream(), C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def bs_debug_attention_shape(q_blocks=0, n_split=0):
+    """Test hook (not part of the public ABI): forces the attention launch shape; 0 = automatic."""
+    f = lib().bs_debug_attention_shape
+    f.argtypes = [C.c_int, C.c_int]
+    f.restype = None
+    f(q_blocks, n_split)

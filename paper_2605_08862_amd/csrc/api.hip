@@ -276,7 +276,7 @@ void bs_destroy(bs_ctx* ctx) {
 
 bs_status bs_profile_begin(bs_ctx* c, int kernel_class) {
   if (!c) return BS_EINVAL;
-  if (kernel_class < BS_PROF_NONE || kernel_class > BS_PROF_LOOKUP) return fail(c, BS_EINVAL, "bs_profile_begin: unknown class");
+  if (kernel_class < BS_PROF_NONE || kernel_class > BS_PROF_EMPTY) return fail(c, BS_EINVAL, "bs_profile_begin: unknown class");
   c->prof_class = kernel_class;
   c->prof_used = 0;
   return BS_OK;
@@ -344,6 +344,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
   int pending = 0;                              // slabs of the last residual projection not yet added to h
   for (int l = 0; l < s.L; ++l) {
+    { ProfScope ps(c, BS_PROF_EMPTY, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->attn_norm[l], c->a, st);
     int nq;
     { ProfScope ps(c, BS_PROF_GEMM_QKV, st);

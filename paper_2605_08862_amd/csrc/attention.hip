@@ -384,6 +384,15 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
                        n_split, (f16*)out);
 }
 
+// Test hook, not part of the public ABI: forces the launch shape of the bf16 attention kernel (0 = choose
+// automatically) so that every instantiation can be exercised at small batch sizes.  A q_blocks value that
+// does not divide the number of query tiles is ignored.
+static int g_force_q_blocks = 0, g_force_n_split = 0;
+extern "C" void bs_debug_attention_shape(int q_blocks, int n_split) {
+  g_force_q_blocks = q_blocks;
+  g_force_n_split = n_split;
+}
+
 void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
                       const void* k_pages, const void* v_pages, void* out, void* scratch, void* prof_token,
                       hipStream_t st) {
@@ -411,9 +420,10 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
   int q_blocks = 1;
   if (tiles == 2 && units < 256) q_blocks = 2;
   if (tiles == 4) q_blocks = units < 128 ? 4 : (units < 256 ? 2 : 1);
-  if (qb_env) { const int v = atoi(qb_env); if (v >= 1 && v <= tiles && tiles % v == 0) q_blocks = v; }
+  const int qb_forced = g_force_q_blocks ? g_force_q_blocks : (qb_env ? atoi(qb_env) : 0);
+  if (qb_forced >= 1 && qb_forced <= tiles && tiles % qb_forced == 0) q_blocks = qb_forced;
   const int wgs = units * q_blocks;
-  int n_split = split_env ? atoi(split_env) : (256 + wgs / 2) / wgs;   // ~ one workgroup per CU
+  int n_split = g_force_n_split ? g_force_n_split : (split_env ? atoi(split_env) : (256 + wgs / 2) / wgs);   // ~ one workgroup per CU
   n_split = n_split < 1 ? 1 : (n_split > kMaxSplit ? kMaxSplit : n_split);
   const int tiles_wg = tiles / q_blocks;                           // query tiles per workgroup: 1, 2 or 4
 #define BS_ATTN(NQ, QG)                                                                                         \

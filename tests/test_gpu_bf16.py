@@ -6,6 +6,7 @@ import pytest
 import torch
 
 from oracle import decoder as OD
+from paper_2605_08862_amd import binding as B
 from paper_2605_08862_amd import workloads as W
 from paper_2605_08862_amd.runtime import Engine, fuse_weights
 from tests import helpers as H
@@ -111,6 +112,30 @@ def test_mini_wide_groups_k16():
 def test_mini_head_dim_64():
     desc = W.shape("mini_bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, vocab=4096)
     _run_case(desc, ctx_lens=[100, 513, 64], k_b=[3, 8, 8], k_max=8, seed=25)
+
+
+@pytest.mark.parametrize("q_blocks,n_split", [(1, 1), (1, 3), (2, 1), (2, 2), (4, 1), (4, 5)])
+def test_attention_launch_shapes_k16(q_blocks, n_split):
+    """The G = 7, k = 16 case (four query tiles per KV head) under every launch shape of the attention kernel:
+    one workgroup per unit with two wave groups (1 query block), two tiles per workgroup (2) and one tile per
+    workgroup (4), each with and without a KV split."""
+    desc = W.shape("mini_bf16", n_q_heads=14, n_kv_heads=2, d_model=320, d_ffn=448, vocab=777)
+    B.bs_debug_attention_shape(q_blocks, n_split)
+    try:
+        _run_case(desc, ctx_lens=[700, 40, 129, 1000, 3], k_b=[16, 0, 9, 12, 16], k_max=16, seed=24)
+    finally:
+        B.bs_debug_attention_shape(0, 0)
+
+
+@pytest.mark.parametrize("q_blocks,n_split,head_dim", [(1, 1, 128), (1, 4, 128), (2, 3, 128), (1, 2, 64), (2, 1, 64)])
+def test_attention_launch_shapes_k8(q_blocks, n_split, head_dim):
+    """Two query tiles per KV head (G = 6, k = 8: 54 rows) as one or two query blocks, head sizes 128 and 64."""
+    desc = W.shape("mini_bf16", head_dim=head_dim, n_q_heads=12, n_kv_heads=2, d_model=384, vocab=1000)
+    B.bs_debug_attention_shape(q_blocks, n_split)
+    try:
+        _run_case(desc, ctx_lens=[1, 63, 64, 200, 333, 0], k_b=[8, 0, 3, 8, 5, 2], k_max=8, seed=31)
+    finally:
+        B.bs_debug_attention_shape(0, 0)
 
 
 def test_slice_1p5b_full_vocab():
