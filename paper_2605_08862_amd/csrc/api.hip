@@ -18,6 +18,7 @@ struct bs_ctx {
   Plan plan;
   float* h;            // residual stream  [M_max, d] float32
   double* inv_freq;    // [D/2] rotary frequencies
+  float *rope_cos, *rope_sin;   // [M_max, D/2] cos / sin of the step's rotary angles
   std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down;         // bf16 models: packed copies in the workspace
   void* pk_lm = nullptr;
   void* a;             // normed rows      [M_max, d] (GEMM operand type: float32 / float16)
@@ -96,6 +97,8 @@ size_t carve(bs_ctx* c, char* base) {
   p.row_target = w.take<int32_t>(M);
   c->h = w.take<float>((size_t)M * s.d);
   c->inv_freq = w.take<double>(64);
+  c->rope_cos = w.take<float>((size_t)M * 64);
+  c->rope_sin = w.take<float>((size_t)M * 64);
   c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
   c->qkv = w.take<float>((size_t)M * s.Nqkv());
   c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
@@ -341,6 +344,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   const Plan& p = c->plan;
   launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, st);
   launch_embed(s, p, M_max, c->embed, c->h, st);
+  launch_rope_angles(s, p, M_max, c->inv_freq, c->rope_cos, c->rope_sin, st);
   const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
   int pending = 0;                              // slabs of the last residual projection not yet added to h
   for (int l = 0; l < s.L; ++l) {
@@ -350,7 +354,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
     { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
       nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
                        slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
-    launch_rope_append(s, p, c->kv, M_max, c->inv_freq, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
+    launch_rope_append(s, p, c->kv, M_max, c->rope_cos, c->rope_sin, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
                        c->v_pages[l], st);
     launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);

@@ -91,22 +91,38 @@ __global__ void rope_table_kernel(int D, float theta, double* __restrict__ inv_f
   if (j < D / 2) inv_freq[j] = exp2(-2.0 * (double)j / (double)D * log2((double)theta));
 }
 
+// cos / sin of the rotary angles of every packed row (absolute position c_b + i), once per step: the table
+// [M_max][D/2] is shared by all layers.  Angles are formed in float64 (at positions of 3e4 a float32 angle
+// is already off by ~2e-3 rad), reduced to [-pi, pi] in float64 and only then handed to the float32 sine /
+// cosine.
+__global__ void __launch_bounds__(64) rope_angles_kernel(Plan p, int D, const double* __restrict__ inv_freq,
+                                                         float* __restrict__ cos_t, float* __restrict__ sin_t) {
+  const int r = blockIdx.x, j = threadIdx.x, half = D / 2;
+  if (r >= p.n_rows[0] || j >= half) return;
+  const int pos = p.seq_c[p.row_seq[r]] + p.row_pos[r];
+  const double ang = (double)pos * inv_freq[j];
+  const double two_pi_hi = 6.283185307179586, two_pi_lo = 2.4492935982947064e-16;
+  const double n = rint(ang * 0.15915494309189535);
+  const double red = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
+  float sn, cs;
+  sincosf((float)red, &sn, &cs);
+  cos_t[(size_t)r * half + j] = cs;
+  sin_t[(size_t)r * half + j] = sn;
+}
+
 // Rotary (pairs (j, j + D/2), angle = position * theta^(-2j/D)) on q and k of packed row r at
-// absolute position c_b + i.  The QKV projection arrives in float32, as n_slabs K-split slabs that are
-// summed here (so each of q, k, v is rounded exactly once, after the rotation): q goes to the query
-// buffer (float16 for bf16 models: it is an attention operand, not cache data), k and v to the slot's
-// page in the cache dtype.
-// Angles are formed in float64 (at positions of 3e4 a float32 angle is already off by ~2e-3 rad), reduced
-// to [-pi, pi] in float64 and only then handed to the float32 sine / cosine.
+// absolute position c_b + i, with the cos / sin table of rope_angles_kernel.  The QKV projection arrives in
+// float32, as n_slabs K-split slabs that are summed here (so each of q, k, v is rounded exactly once, after
+// the rotation): q goes to the query buffer (float16 for bf16 models: it is an attention operand, not
+// cache data), k and v to the slot's page in the cache dtype.
 // One workgroup per row; a work item is four consecutive rotation pairs of one head (two 16-byte loads
 // per slab, 8-byte stores) or four consecutive v elements.
 template <typename T, typename TQ, typename TP>
 __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int Hq, int Hkv, int D,
-                                                          const double* __restrict__ inv_freq,
+                                                          const float* __restrict__ cos_t, const float* __restrict__ sin_t,
                                                           const float* __restrict__ qkv, int n_slabs, size_t slab_stride,
                                                           TQ* __restrict__ q_out, TP* __restrict__ k_pages,
                                                           TP* __restrict__ v_pages) {
-  __shared__ float s_cos[64], s_sin[64];
   typedef float f4 __attribute__((ext_vector_type(4)));
   const int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
@@ -115,46 +131,22 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
   const int half = D / 2, groups = half / 4;
   const float* row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
   const int n_rot = (Hq + Hkv) * groups, n_items = n_rot + Hkv * D / 4;
-  // first item of this thread: loads are issued before the angle computation and the barrier
-  const int idx0 = threadIdx.x;
-  f4 a0 = f4{0.f, 0.f, 0.f, 0.f}, b0 = a0;
-  int hh0 = 0, j0 = 0;
-  if (idx0 < n_rot) {
-    hh0 = idx0 / groups; j0 = (idx0 % groups) * 4;
-    const float* x = row + (size_t)hh0 * D + j0;
-    for (int sl = 0; sl < n_slabs; ++sl) { a0 += *(const f4*)(x + sl * slab_stride); b0 += *(const f4*)(x + sl * slab_stride + half); }
-  }
-  if (threadIdx.x < half) {
-    const double ang = (double)pos * inv_freq[threadIdx.x];
-    const double two_pi_hi = 6.283185307179586, two_pi_lo = 2.4492935982947064e-16;
-    const double n = rint(ang * 0.15915494309189535);
-    const double red = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
-    float sn, cs;
-    sincosf((float)red, &sn, &cs);
-    s_cos[threadIdx.x] = cs;
-    s_sin[threadIdx.x] = sn;
-  }
-  __syncthreads();
   TQ* qrow = q_out + (size_t)r * Hq * D;
   const int page = kv.block_table[(size_t)p.seq_slot[b] * kv.max_pages + pos / kPage];
   const int tok = pos % kPage;
   const size_t pbase = (size_t)page * kv_page_elems(Hkv, D);
-  for (int idx = idx0; idx < n_items; idx += 256) {
+  for (int idx = threadIdx.x; idx < n_items; idx += 256) {
     if (idx < n_rot) {
-      int hh = hh0, j = j0;
-      f4 x1 = a0, x2 = b0;
-      if (idx != idx0) {
-        hh = idx / groups; j = (idx % groups) * 4;
-        const float* x = row + (size_t)hh * D + j;
-        x1 = f4{0.f, 0.f, 0.f, 0.f}; x2 = x1;
-        for (int sl = 0; sl < n_slabs; ++sl) { x1 += *(const f4*)(x + sl * slab_stride); x2 += *(const f4*)(x + sl * slab_stride + half); }
-      }
+      const int hh = idx / groups, j = (idx % groups) * 4;
+      const float* x = row + (size_t)hh * D + j;
+      f4 x1 = f4{0.f, 0.f, 0.f, 0.f}, x2 = x1;
+      for (int sl = 0; sl < n_slabs; ++sl) { x1 += *(const f4*)(x + sl * slab_stride); x2 += *(const f4*)(x + sl * slab_stride + half); }
+      const f4 c = *(const f4*)(cos_t + (size_t)r * half + j), sn = *(const f4*)(sin_t + (size_t)r * half + j);
       float y1[4], y2[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float c = s_cos[j + e], sn = s_sin[j + e];
-        y1[e] = x1[e] * c - x2[e] * sn;
-        y2[e] = x2[e] * c + x1[e] * sn;
+        y1[e] = x1[e] * c[e] - x2[e] * sn[e];
+        y2[e] = x2[e] * c[e] + x1[e] * sn[e];
       }
       if (hh < Hq) {
 #pragma unroll
@@ -225,14 +217,18 @@ void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const fl
 void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st) {
   hipLaunchKernelGGL(rope_table_kernel, dim3(1), dim3(64), 0, st, s.D, s.theta, inv_freq);
 }
-void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const double* inv_freq,
+void launch_rope_angles(const Shape& s, const Plan& p, int M_max, const double* inv_freq, float* cos_t, float* sin_t,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(rope_angles_kernel, dim3(M_max), dim3(64), 0, st, p, s.D, inv_freq, cos_t, sin_t);
+}
+void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* cos_t, const float* sin_t,
                         const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
   const size_t stride = (size_t)M_max * s.Nqkv();
   if (s.dtype == BS_F32)
-    hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, inv_freq,
+    hipLaunchKernelGGL((rope_append_kernel<float, float, float>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, cos_t, sin_t,
                        qkv, n_slabs, stride, (float*)q_out, (float*)k_pages, (float*)v_pages);
   else
-    hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, inv_freq,
+    hipLaunchKernelGGL((rope_append_kernel<bf16, f16, f16>), dim3(M_max), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, cos_t, sin_t,
                        qkv, n_slabs, stride, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
