@@ -209,3 +209,11 @@ def bs_debug_attention_shape(q_blocks=0, n_split=0):
     f.argtypes = [C.c_int, C.c_int]
     f.restype = None
     f(q_blocks, n_split)
+
+
+def bs_debug_unfused_qkv(ctx, on):
+    """Test hook (not part of the public ABI): use the QKV GEMM + separate rotary kernel instead of the fused one."""
+    f = lib().bs_debug_unfused_qkv
+    f.argtypes = [C.c_void_p, C.c_int]
+    f.restype = None
+    f(ctx, 1 if on else 0)

@@ -39,6 +39,7 @@ struct bs_ctx {
   const int32_t* prompt_rollout_begin = nullptr;
   // measurement hooks
   int prof_class = 0;
+  bool unfused_qkv = false;   // test hook: QKV GEMM + separate rotary kernel instead of the fused kernel
   std::vector<hipEvent_t> prof_ev;     // pairs (start, stop), created on first use
   size_t prof_used = 0;
   hipEvent_t prof_pending_stop = nullptr;
@@ -350,12 +351,17 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   for (int l = 0; l < s.L; ++l) {
     { ProfScope ps(c, BS_PROF_EMPTY, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->attn_norm[l], c->a, st);
-    int nq;
-    { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
-      nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
-                       slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
-    launch_rope_append(s, p, c->kv, M_max, c->rope_cos, c->rope_sin, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q, c->k_pages[l],
-                       c->v_pages[l], st);
+    if (qkv_rope_supported(s) && !c->unfused_qkv) {
+      ProfScope ps(c, BS_PROF_GEMM_QKV, st);
+      launch_qkv_rope(s, p, c->kv, M_max, c->a, c->wqkv[l], c->rope_cos, c->rope_sin, c->q, c->k_pages[l], c->v_pages[l], st);
+    } else {
+      int nq;
+      { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
+        nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
+                         slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
+      launch_rope_append(s, p, c->kv, M_max, c->rope_cos, c->rope_sin, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q,
+                         c->k_pages[l], c->v_pages[l], st);
+    }
     launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
     { ProfScope ps(c, BS_PROF_GEMM_O, st);
@@ -508,6 +514,10 @@ bs_status bs_poll_status(bs_ctx* c, void* stream, int32_t* fault_out) {
   *fault_out = host;
   return check_hip(c);
 }
+
+// Not part of the public ABI: selects the unfused QKV path (projection GEMM, then the rotary / append kernel)
+// for models that would use the fused kernel, so that tests cover both.
+void bs_debug_unfused_qkv(bs_ctx* c, int on) { if (c) c->unfused_qkv = on != 0; }
 
 // Not part of the public ABI: address of an intermediate buffer of the last verify step, for
 // kernel-level debugging (0 h, 1 normed rows, 2 qkv f32, 3 q, 4 attention out, 5 mlp act, 6 final rows).

@@ -116,6 +116,11 @@ void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_m
                         const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
                     void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
+// qkv_rope.hip   QKV projection + rotary + KV append in one kernel (bf16 models with head size 128); A = normed
+// rows (float16), Wp = packed wqkv.
+bool qkv_rope_supported(const Shape& s);
+void launch_qkv_rope(const Shape& s, const Plan& p, const KvView& kv, int M_max, const void* A, const void* Wp,
+                     const float* cos_t, const float* sin_t, void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 // gemm.hip   C[M,N] (+)= A[M,K] * W[N,K]^T with an epilogue.  float32 models: A, W float32 row-major.
 // bf16 models: A float16 row-major, W the packed float16 copy made by launch_pack_weight.
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3 };

@@ -22,7 +22,7 @@ def _f64_weights(wn):
 
 
 def _run_case(desc, ctx_lens, k_b, k_max, seed, temperature=1.0, q_mode="dense", q_scale=0.8, perm=3,
-              check_kv=True):
+              check_kv=True, unfused_qkv=False):
     """One verify step on random-filled contexts; returns stats after asserting all three tiers."""
     Bn = len(ctx_lens)
     rng = np.random.default_rng(seed)
@@ -31,6 +31,8 @@ def _run_case(desc, ctx_lens, k_b, k_max, seed, temperature=1.0, q_mode="dense",
     wn = _f64_weights(W.weights_to_numpy(w))
     eng = Engine(desc, fuse_weights(w, desc["dtype"], DEV), Bn, int(max(ctx_lens)) + k_max + 1, B_max=Bn,
                  k_max=k_max, page_perm_seed=perm)
+    if unfused_qkv:
+        B.bs_debug_unfused_qkv(eng.ctx, True)
     od = H.oracle_desc(desc)
     caches = []
     for b in range(Bn):
@@ -95,6 +97,14 @@ def _run_case(desc, ctx_lens, k_b, k_max, seed, temperature=1.0, q_mode="dense",
 def test_mini_ragged_dense_q():
     desc = W.shape("mini_bf16")
     _run_case(desc, ctx_lens=[1, 63, 64, 200, 333, 0, 31, 97], k_b=[8, 0, 3, 8, 5, 2, 1, 7], k_max=8, seed=21)
+
+
+def test_mini_unfused_qkv_path():
+    """Head size 128 normally takes the fused QKV + rotary + append kernel; this runs the same case through
+    the projection GEMM followed by the separate rotary / append kernel."""
+    desc = W.shape("mini_bf16")
+    _run_case(desc, ctx_lens=[1, 63, 64, 200, 333, 0, 31, 97], k_b=[8, 0, 3, 8, 5, 2, 1, 7], k_max=8, seed=21,
+              unfused_qkv=True)
 
 
 def test_mini_one_hot_and_temperature():
