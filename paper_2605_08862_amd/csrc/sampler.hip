@@ -7,6 +7,7 @@
 //            recomputed by the same MFMA loop (bit-identical logits) and sampled by inverse CDF in
 //            vocabulary order with float64 running sums (Eq. 3 / max(0, p - q)).
 #include "gemm_mfma.h"
+#include <stdlib.h>
 
 enum { MODE_NONE = 0, MODE_PLAIN = 1, MODE_RESID_ONEHOT = 2, MODE_RESID_DENSE = 3 };
 
@@ -25,7 +26,7 @@ int lmhead_vtiles(int V) {
 // STATS = false: rows are gathered through sel_row (one per sequence); epilogue stores float32 logits
 //                to sel_logits [B, V].
 template <int kLmMT, bool STATS>
-__global__ void __launch_bounds__(256) lmhead_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int V, int K,
+__global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int V, int K,
                                                      const f16* __restrict__ X, const int32_t* __restrict__ x_rows,
                                                      const f16* __restrict__ W, float inv_temp,
                                                      const int32_t* __restrict__ row_target, SamplerBufs sb,
@@ -508,11 +509,21 @@ template <bool STATS>
 static void launch_lmhead_any(const Shape& s, const int32_t* n_rows_dev, int M_max, const void* hf, const int32_t* x_rows,
                               const void* lm_head, float inv_temp, const int32_t* row_target, const SamplerBufs& sb,
                               float* store, hipStream_t st) {
-  if (M_max <= 32) launch_lmhead_t<1, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
-  else if (M_max <= 64) launch_lmhead_t<2, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
-  else if (M_max <= 128 || (M_max + 127) / 128 * 128 < (M_max + 191) / 192 * 192)
-    launch_lmhead_t<4, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
-  else launch_lmhead_t<6, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st);
+  // Row tiling.  The vocabulary gives thousands of workgroups (many rounds per CU), so above 128 rows the
+  // 96-row tile is used: it fits two workgroups per CU, and the statistics epilogue and the pipeline fill of
+  // one overlap the matrix products of the other (measured at M = 576, V = 151936: 308 us against 372 us with
+  // 192-row tiles, one workgroup per CU).
+  static const char* env_mt = getenv("BS_LM_MT");                  // tuning aid
+  const int mt = env_mt ? atoi(env_mt) : (M_max <= 32 ? 1 : M_max <= 64 ? 2 : M_max <= 128 ? 4 : 3);
+#define BS_LM(MT_) launch_lmhead_t<MT_, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st)
+  switch (mt) {
+    case 1: BS_LM(1); break;
+    case 2: BS_LM(2); break;
+    case 4: BS_LM(4); break;
+    case 6: BS_LM(6); break;
+    default: BS_LM(3);
+  }
+#undef BS_LM
 }
 void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head, float inv_temp,
                          const SamplerBufs& sb, float* logits_debug, hipStream_t st) {
