@@ -209,7 +209,8 @@ bs_status bs_kv_read(bs_ctx* ctx, int layer, int slot, int pos0, int n, void* k_
 enum {
   BS_PROF_NONE = 0,
   BS_PROF_ATTENTION = 1,   /* ragged verify attention (bf16 models: the MFMA kernel, merge excluded) */
-  BS_PROF_GEMM_QKV = 2,
+  BS_PROF_GEMM_QKV = 2,    /* QKV projection (bf16 models with head size 128: the kernel that also applies the
+                              rotary embedding and appends K/V) */
   BS_PROF_GEMM_O = 3,
   BS_PROF_GEMM_GATE_UP = 4,
   BS_PROF_GEMM_DOWN = 5,
