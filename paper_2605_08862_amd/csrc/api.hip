@@ -115,6 +115,9 @@ size_t carve(bs_ctx* c, char* base) {
   sb.part_max = w.take<float>((size_t)c->n_vtiles * M);
   sb.part_sum = w.take<float>((size_t)c->n_vtiles * M);
   sb.part_arg = w.take<int32_t>((size_t)c->n_vtiles * M);
+  sb.fold_max = w.take<float>((size_t)16 * M);
+  sb.fold_sum = w.take<float>((size_t)16 * M);
+  sb.fold_arg = w.take<int32_t>((size_t)16 * M);
   sb.z_target = w.take<float>(M);
   sb.row_max = w.take<float>(M);
   sb.row_lse = w.take<float>(M);

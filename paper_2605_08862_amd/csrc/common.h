@@ -142,6 +142,7 @@ size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
 // sampler.hip
 struct SamplerBufs {
   float* part_max; float* part_sum; int32_t* part_arg;   // [n_vtiles, M_max]
+  float* fold_max; float* fold_sum; int32_t* fold_arg;   // [16, M_max] tile entries folded over 16 vocabulary ranges
   float* z_target;                                       // [M_max] logit of the judged draft token
   float* row_max; float* row_lse; int32_t* row_arg;      // [M_max] combined statistics of each packed row
   float* q_max; float* q_lse; float* q_target;           // [M_max] per query row that judges a draft

@@ -169,9 +169,43 @@ __global__ void __launch_bounds__(256) logit_stats_kernel(Plan p, int M_max, int
 }
 
 // ------------------------------------------------------------------ per-row statistics
-// Combines the per-tile (max, sum exp, arg max) of one packed row: row_max (raw logit), row_lse of z/T,
-// row_arg (first arg max).  One workgroup per row; tile entries of a row are M_max apart.
-__global__ void __launch_bounds__(256) row_stats_kernel(Plan p, int M_max, int n_vtiles, float inv_temp, SamplerBufs sb) {
+// Stage 1 folds the per-tile (max, sum exp, arg max) entries of 32 consecutive rows over one of kStatChunks
+// ranges of vocabulary tiles into one entry per (row, range) with the same meaning.  Tile entries of a row
+// are M_max apart, so a workgroup reads 32 rows x 8 tiles at a time: every 128-byte line it touches is used
+// completely (one workgroup per row touched a new line for every 4-byte entry: 175 MB fetched for 16 MB).
+constexpr int kStatChunks = 16;
+__global__ void __launch_bounds__(256) row_stats_fold_kernel(Plan p, int M_max, int n_vtiles, float inv_temp, SamplerBufs sb) {
+  __shared__ float s_mx[8][32], s_sum[8][32];
+  __shared__ int s_arg[8][32];
+  const int rr = threadIdx.x & 31, vl = threadIdx.x >> 5;
+  const int r = blockIdx.x * 32 + rr, ch = blockIdx.y;
+  const int per = (n_vtiles + kStatChunks - 1) / kStatChunks;
+  const int v0 = min(ch * per, n_vtiles), v1 = min(v0 + per, n_vtiles);
+  const bool valid = r < min(p.n_rows[0], M_max);
+  float mx = -INFINITY, sum = 0.f;
+  int arg = 0x7fffffff;
+  auto fold = [&](float m2, float s2, int a2) {
+    if (m2 > mx) { sum = sum * __expf((mx - m2) * inv_temp) + s2; mx = m2; arg = a2; }
+    else if (m2 > -INFINITY) { sum += s2 * __expf((m2 - mx) * inv_temp); if (m2 == mx && a2 < arg) arg = a2; }
+  };
+  if (valid)
+    for (int vt = v0 + vl; vt < v1; vt += 8) {
+      const size_t o = (size_t)vt * M_max + r;
+      fold(sb.part_max[o], sb.part_sum[o], sb.part_arg[o]);
+    }
+  s_mx[vl][rr] = mx; s_sum[vl][rr] = sum; s_arg[vl][rr] = arg;
+  __syncthreads();
+  if (vl == 0 && valid) {
+    for (int w = 1; w < 8; ++w) fold(s_mx[w][rr], s_sum[w][rr], s_arg[w][rr]);
+    const size_t o = (size_t)ch * M_max + r;
+    sb.fold_max[o] = mx; sb.fold_sum[o] = sum; sb.fold_arg[o] = arg;
+  }
+}
+
+// Stage 2 (also the only stage for the few 1024-entry tiles of the plain-logits path):
+__global__ void __launch_bounds__(256) row_stats_kernel(Plan p, int M_max, int n_vtiles, float inv_temp, SamplerBufs sb,
+                                                        const float* __restrict__ t_max, const float* __restrict__ t_sum,
+                                                        const int32_t* __restrict__ t_arg) {
   __shared__ float s_mx[4], s_sum[4];
   __shared__ int s_arg[4];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -179,8 +213,8 @@ __global__ void __launch_bounds__(256) row_stats_kernel(Plan p, int M_max, int n
   float mx = -INFINITY;
   int arg = 0x7fffffff;
   for (int vt = tid; vt < n_vtiles; vt += 256) {
-    const float m2 = sb.part_max[(size_t)vt * M_max + r];
-    const int a2 = sb.part_arg[(size_t)vt * M_max + r];
+    const float m2 = t_max[(size_t)vt * M_max + r];
+    const int a2 = t_arg[(size_t)vt * M_max + r];
     if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
   }
   for (int o = 32; o > 0; o >>= 1) {
@@ -195,8 +229,8 @@ __global__ void __launch_bounds__(256) row_stats_kernel(Plan p, int M_max, int n
     if (s_mx[w] > mx || (s_mx[w] == mx && s_arg[w] < arg)) { mx = s_mx[w]; arg = s_arg[w]; }
   float sum = 0.f;
   for (int vt = tid; vt < n_vtiles; vt += 256) {
-    const float m2 = sb.part_max[(size_t)vt * M_max + r];
-    if (m2 > -INFINITY) sum += sb.part_sum[(size_t)vt * M_max + r] * __expf((m2 - mx) * inv_temp);
+    const float m2 = t_max[(size_t)vt * M_max + r];
+    if (m2 > -INFINITY) sum += t_sum[(size_t)vt * M_max + r] * __expf((m2 - mx) * inv_temp);
   }
   for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
   if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
@@ -230,18 +264,33 @@ __global__ void __launch_bounds__(256) q_stats_kernel(Plan p, int V, const Q* __
     if (x > m) { sum = sum * __expf(m - x) + 1.0f; m = x; }   // exp(-inf) = 0 on the first element
     else sum += __expf(x - m);
   };
-  const bool aligned = (((uintptr_t)q) & 15) == 0;
-  const int nvec = aligned ? V / N : 0;
-  for (int i = tid; i < nvec; i += 256) {
-    const u32x4 raw = *(const u32x4*)(q + (size_t)i * N);
+  // one 16-byte vector: a single rescale for its maximum, then N exponentials
+  auto absorb_vec = [&](const u32x4 raw) {
+    float x[N];
     if (N == 4) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) absorb(__uint_as_float(raw[j]));
+      for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(raw[j]);
     } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { absorb(__uint_as_float(raw[j] << 16)); absorb(__uint_as_float(raw[j] & 0xffff0000u)); }
+      for (int j = 0; j < 4; ++j) { x[2 * j] = __uint_as_float(raw[j] << 16); x[2 * j + 1] = __uint_as_float(raw[j] & 0xffff0000u); }
     }
+    float vm = x[0];
+#pragma unroll
+    for (int j = 1; j < N; ++j) vm = fmaxf(vm, x[j]);
+    if (vm == -INFINITY) return;
+    if (vm > m) { sum *= __expf(m - vm); m = vm; }
+#pragma unroll
+    for (int j = 0; j < N; ++j) sum += __expf(x[j] - m);
+  };
+  const bool aligned = (((uintptr_t)q) & 15) == 0;
+  const int nvec = aligned ? V / N : 0;
+  int i = tid;
+  for (; i + 768 < nvec; i += 1024) {                  // four vectors in flight per thread
+    const u32x4 r0 = *(const u32x4*)(q + (size_t)i * N), r1 = *(const u32x4*)(q + (size_t)(i + 256) * N);
+    const u32x4 r2 = *(const u32x4*)(q + (size_t)(i + 512) * N), r3 = *(const u32x4*)(q + (size_t)(i + 768) * N);
+    absorb_vec(r0); absorb_vec(r1); absorb_vec(r2); absorb_vec(r3);
   }
+  for (; i < nvec; i += 256) absorb_vec(*(const u32x4*)(q + (size_t)i * N));
   for (int n = nvec * N + tid; n < V; n += 256) absorb(to_f32<Q>(q[n]));
   for (int o = 32; o > 0; o >>= 1) {
     const float mo = __shfl_xor(m, o), so = __shfl_xor(sum, o);
@@ -547,7 +596,14 @@ void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles
                         int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
                         int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
   const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
-  hipLaunchKernelGGL(row_stats_kernel, dim3(M_max), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb);
+  if (n_vtiles > 4 * kStatChunks) {
+    hipLaunchKernelGGL(row_stats_fold_kernel, dim3((M_max + 31) / 32, kStatChunks), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(M_max), dim3(256), 0, st, p, M_max, kStatChunks, inv_temp, sb, sb.fold_max,
+                       sb.fold_sum, sb.fold_arg);
+  } else {
+    hipLaunchKernelGGL(row_stats_kernel, dim3(M_max), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb, sb.part_max,
+                       sb.part_sum, sb.part_arg);
+  }
   hipLaunchKernelGGL(accept_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, st, p, B, k_max, dense_q ? 1 : 0, temperature,
                      eos_id, emit_bonus, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
 }
