@@ -58,14 +58,30 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(int n_prompts, const i
   // needs no second pass
   if (tid == 0) { s_ncand[0] = 0; s_ncand[1] = 0; }
   __syncthreads();
+  // kScan positions per thread and iteration: their tokens are requested together and only positions whose
+  // token equals the newest context token go on to the full comparison (one dependent load per position
+  // and iteration left the scan bound by memory latency)
+  constexpr int kScan = 8;
+  const int newest = mm > 0 ? s_ctx[max_match - 1] : -2;     // pool tokens are >= 0
   for (int r = r_begin; r < r_end; ++r) {
     const long long s0 = ro[r], s1 = ro[r + 1];
-    for (long long e = s0 + tid; e < s1; e += kThreads) {
-      int len = match_len(e, s0);
-      if (len >= min_match) {
-        atomicAdd(&s_cnt[len], 1);
-        int i = atomicAdd(&s_ncand[1], 1);             // total count (may exceed the capacity)
-        if (i < kCap) { s_pos[1][i] = (int)(e - base); s_end[1][i] = (int)(s1 - base); s_htok[i] = len; }
+    for (long long e0 = s0 + tid; e0 < s1; e0 += (long long)kThreads * kScan) {
+      int tok[kScan];
+#pragma unroll
+      for (int u = 0; u < kScan; ++u) {
+        const long long e = e0 + (long long)u * kThreads;
+        tok[u] = e < s1 ? pool[e] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kScan; ++u) {
+        if (tok[u] != newest) continue;
+        const long long e = e0 + (long long)u * kThreads;
+        int len = match_len(e, s0);
+        if (len >= min_match) {
+          atomicAdd(&s_cnt[len], 1);
+          int i = atomicAdd(&s_ncand[1], 1);           // total count (may exceed the capacity)
+          if (i < kCap) { s_pos[1][i] = (int)(e - base); s_end[1][i] = (int)(s1 - base); s_htok[i] = len; }
+        }
       }
     }
   }

@@ -113,12 +113,22 @@ __global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const
       }
     } else {
       if (!valid) continue;
+      // registers 4 i4 .. 4 i4 + 3 of a lane are four consecutive vocabulary entries: 16-byte stores when the
+      // row pitch keeps them aligned
+      const bool vec = (V & 3) == 0;
 #pragma unroll
       for (int ni = 0; ni < kLmNT; ++ni)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int n = n_wave0 + ni * 32 + acc_row(lane, i);
-          if (n < V) store[(size_t)m * V + n] = acc[mi][ni][i];
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int n = n_wave0 + ni * 32 + acc_row(lane, 4 * i4);
+          if (vec && n + 3 < V) {
+            *(f32x4*)(store + (size_t)m * V + n) =
+                f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < V) store[(size_t)m * V + n + e] = acc[mi][ni][4 * i4 + e];
+          }
         }
     }
   }
