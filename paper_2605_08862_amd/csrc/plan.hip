@@ -11,51 +11,75 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
                                                    const int32_t* __restrict__ draft_tokens,
                                                    const int32_t* __restrict__ draft_len, int need_kv) {
   __shared__ int s_fault;
+  __shared__ int s_slot[4096];                      // B <= 4096 (checked at context creation)
+  __shared__ int s_k[4096];                         // validated k_b (-1: skipped)
+  __shared__ int s_pr[256], s_pt[256];              // per-thread partial row / draft counts, then their prefix
   const int tid = threadIdx.x;
   if (tid == 0) s_fault = 0;
+  if (need_kv)
+    for (int b = tid; b < B; b += blockDim.x) s_slot[b] = seq_slot[b];
   __syncthreads();
-  // phase 1: per-sequence validation (parallel over sequences)
+  // phase 1: per-sequence validation (parallel over sequences).  Global loads are requested eight at a time:
+  // one dependent load per loop iteration made this kernel latency-bound (33 pages per sequence at context 2048).
   for (int b = tid; b < B; b += blockDim.x) {
     int k = draft_len[b], fault = 0, c = 0, slot = 0;
     if (k < 0 || k > k_max) { fault |= BS_FAULT_DRAFT_LEN; }
     if (need_kv) {
-      slot = seq_slot[b];
+      slot = s_slot[b];
       if (slot < 0 || slot >= kv.n_slots) {
         fault |= BS_FAULT_SLOT;
       } else {
-        for (int b2 = 0; b2 < b; ++b2) if (seq_slot[b2] == slot) fault |= BS_FAULT_SLOT;
+        for (int b2 = 0; b2 < b; ++b2) if (s_slot[b2] == slot) fault |= BS_FAULT_SLOT;
         c = kv.ctx_len[slot];
         if (!(fault & BS_FAULT_DRAFT_LEN)) {
           if (c < 0 || (long)c + k + 1 > (long)kv.max_pages * kPage) {
             fault |= BS_FAULT_KV_PAGES;
           } else {
-            for (int pg = 0; pg <= (c + k) / kPage; ++pg) {
-              int id = kv.block_table[(size_t)slot * kv.max_pages + pg];
-              if (id < 0 || id >= kv.n_pages) fault |= BS_FAULT_KV_PAGES;
+            const int32_t* bt = kv.block_table + (size_t)slot * kv.max_pages;
+            const int last = (c + k) / kPage;
+            for (int pg0 = 0; pg0 <= last; pg0 += 8) {
+              int id[8];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) id[u] = bt[min(pg0 + u, last)];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) if (id[u] < 0 || id[u] >= kv.n_pages) fault |= BS_FAULT_KV_PAGES;
             }
           }
         }
       }
     }
     p.seq_k[b] = fault ? -1 : k;
+    s_k[b] = fault ? -1 : k;
     p.seq_c[b] = c;
     p.seq_slot[b] = slot;
     if (fault) atomicOr(&s_fault, fault);
   }
   __syncthreads();
-  // phase 2: prefix sums (B is small; one thread)
+  // phase 2: prefix sums over the sequences (each thread a contiguous range, partials scanned by thread 0)
+  const int per = (B + 255) / 256;
+  const int b_lo = min(tid * per, B), b_hi = min(b_lo + per, B);
+  {
+    int r = 0, t = 0;
+    for (int b = b_lo; b < b_hi; ++b) if (s_k[b] >= 0) { r += s_k[b] + 1; t += s_k[b]; }
+    s_pr[tid] = r; s_pt[tid] = t;
+  }
+  __syncthreads();
   if (tid == 0) {
     int r = 0, t = 0;
-    for (int b = 0; b < B; ++b) {
-      p.row_start[b] = r;
-      p.draft_start[b] = t;
-      int k = p.seq_k[b];
-      if (k >= 0) { r += k + 1; t += k; }
-    }
+    for (int i = 0; i < 256; ++i) { const int a = s_pr[i], c2 = s_pt[i]; s_pr[i] = r; s_pt[i] = t; r += a; t += c2; }
     p.row_start[B] = r;
     p.draft_start[B] = t;
     p.n_rows[0] = r;
     p.n_rows[1] = t;
+  }
+  __syncthreads();
+  {
+    int r = s_pr[tid], t = s_pt[tid];
+    for (int b = b_lo; b < b_hi; ++b) {
+      p.row_start[b] = r;
+      p.draft_start[b] = t;
+      if (s_k[b] >= 0) { r += s_k[b] + 1; t += s_k[b]; }
+    }
   }
   __syncthreads();
   // phase 3: per-row maps (parallel over sequences x positions)
