@@ -36,6 +36,8 @@ def test_workspace_query_and_shape_validation(lib):
                 dict(ok, dtype=7), dict(ok, vocab=1)):
         assert B.bs_workspace_bytes(B.make_desc(bad), 4, 4) == 0
     assert B.bs_workspace_bytes(B.make_desc(ok), 0, 4) == 0
+    assert B.bs_workspace_bytes(B.make_desc(dict(ok, d_model=16384)), 4, 4) > 0
+    assert B.bs_workspace_bytes(B.make_desc(dict(ok, d_model=16384 + 64)), 4, 4) == 0     # row kept in registers
     assert B.bs_workspace_bytes(B.make_desc(ok), 4, B.BS_MAX_K + 1) == 0
     big = dict(n_layers=28, d_model=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, d_ffn=18944, vocab=152064,
                dtype=B.BS_BF16)

@@ -119,6 +119,13 @@ def test_mini_wide_groups_k16():
     _run_case(desc, ctx_lens=[700, 40, 129, 1000, 3], k_b=[16, 0, 9, 12, 16], k_max=16, seed=24)
 
 
+def test_mini_maximum_draft_length():
+    """k_max = 30 (the library's maximum) with G = 3: up to 93 query rows per KV head, i.e. three of the four
+    query tiles are populated and the fourth block of workgroups exits at once; ragged lengths down to 0."""
+    desc = W.shape("mini_bf16")
+    _run_case(desc, ctx_lens=[90, 3, 500, 64], k_b=[30, 0, 17, 29], k_max=30, seed=33)
+
+
 def test_mini_head_dim_64():
     desc = W.shape("mini_bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, vocab=4096)
     _run_case(desc, ctx_lens=[100, 513, 64], k_b=[3, 8, 8], k_max=8, seed=25)
