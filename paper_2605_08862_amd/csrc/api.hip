@@ -96,6 +96,11 @@ size_t carve(bs_ctx* c, char* base) {
   p.row_pos = w.take<int32_t>(M);
   p.row_tok = w.take<int32_t>(M);
   p.row_target = w.take<int32_t>(M);
+  p.attn_meta = w.take<int32_t>(64);
+  p.item_start = w.take<int32_t>(B + 1);
+  p.item_seq = w.take<int32_t>(attn_item_capacity(B, kAttnMaxSmin));
+  p.item_chunk = w.take<int32_t>(attn_item_capacity(B, kAttnMaxSmin));
+  p.attn_queue = w.take<int32_t>((size_t)8 * s.L);
   c->h = w.take<float>((size_t)M * s.d);
   c->inv_freq = w.take<double>(64);
   c->rope_cos = w.take<float>((size_t)M * 64);
@@ -268,6 +273,7 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   c->final_norm = w->final_norm;
   c->kv = KvView{kv->n_pages, kv->n_slots, kv->max_pages_per_seq, kv->block_table, kv->ctx_len};
   launch_rope_table(c->s, c->inv_freq, (hipStream_t)stream);
+  launch_attention_init(c->s, c->B_max, c->attn_scratch, (hipStream_t)stream);
   launch_clear_status(c->plan.status, (hipStream_t)stream);
   st = check_hip(c);
   if (st != BS_OK) { delete c; return st; }
@@ -346,7 +352,9 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   const Shape& s = c->s;
   const int M_max = B * (k_max + 1);
   const Plan& p = c->plan;
-  launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, st);
+  int attn_s_min, attn_force;
+  attention_plan_params(s, B, k_max, &attn_s_min, &attn_force);
+  launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, attn_s_min, attn_force, s.L, st);
   launch_embed(s, p, M_max, c->embed, c->h, st);
   launch_rope_angles(s, p, M_max, c->inv_freq, c->rope_cos, c->rope_sin, st);
   const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
@@ -365,7 +373,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
       launch_rope_append(s, p, c->kv, M_max, c->rope_cos, c->rope_sin, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q,
                          c->k_pages[l], c->v_pages[l], st);
     }
-    launch_attention(s, p, c->kv, B, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
+    launch_attention(s, p, c->kv, l, B, c->B_max, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
     { ProfScope ps(c, BS_PROF_GEMM_O, st);
       pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l],
@@ -403,7 +411,7 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
   bool rows_selected = false;
   int n_vtiles;
   if (given_logits) {
-    launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, st);
+    launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, 0, 0, 0, st);
     launch_logit_stats(p, M_max, V, given_logits, inv_temp, c->sb, st);
     n_vtiles = (V + 1023) / 1024;
     sample_base = given_logits;

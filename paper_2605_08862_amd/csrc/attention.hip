@@ -3,13 +3,18 @@
 // sequence b attends to cache positions 0 .. c_b + i.
 //
 // MI355X design (bf16 models).  The kernel is HBM-bound: it must stream the committed K/V once.
-//   * A workgroup owns (sequence, KV head, KV split, query block).  All (k_b+1)*G query rows that
+//   * A workgroup owns (sequence, KV head, token chunk, query block).  All (k_b+1)*G query rows that
 //     share the KV head are packed into 32-row MFMA tiles, so K/V are read from HBM once for all of
 //     them (the paper's point: the extra draft rows ride in the matrix tile for free).  When there
 //     are too few (sequence, KV head) units for 256 CUs, the query tiles of a unit go to different
 //     workgroups placed on one XCD (shared L2) rather than splitting the token range: no partial
-//     results, no merge kernel (measured, batch 64 x 2 KV heads, context 2048: 31 us against 35 us +
-//     a 6.6 us merge kernel for the two-way token split).
+//     results (measured, batch 64 x 2 KV heads, context 2048: 31 us against 35 us + a 6.6 us merge
+//     kernel for a two-way token split).
+//   * Token chunks come from the step's work list (plan_kernel): one common chunk size for the whole
+//     batch, so a 32768-token sequence next to 512-token ones becomes many equal work items instead of
+//     one workgroup that runs 60 times longer than the others.  A sequence with one chunk writes its
+//     rows directly; with several, every workgroup stores a float32 partial (+ max, sum) and the LAST
+//     one to finish (device-scope counter, no waiting anywhere) merges them.
 //   * The 4 waves of a workgroup take different 32-token tiles; each keeps its own online-softmax
 //     state (running max m, sum l) and output accumulator and they are merged once at the end.
 //   * K/V pages are stored in MFMA operand order (see common.h), so a wave's 16-byte-per-lane
@@ -28,7 +33,6 @@
 #include <type_traits>
 
 namespace {
-constexpr int kMaxSplit = 16;
 
 __device__ __forceinline__ f16x8 pack_f16x8(const float* v) {
   f16x8 r;
@@ -40,19 +44,29 @@ __device__ __forceinline__ f16x8 pack_f16x8(const float* v) {
 
 // NQ: query-row tiles (of 32) handled by one wave; QG: groups of waves, each group owning NQ of the
 // workgroup's NQ*QG query tiles (tokens are split across the 4/QG waves of a group).
-// A (sequence, KV head) unit is covered by n_split * q_blocks workgroups: KV split `split` of the token
-// range times query block `qb` (NQ*QG query tiles each).  Workgroups of different query blocks stream the
-// same K/V; the one-dimensional grid is decoded so that all workgroups of a unit run on the same XCD
-// (ids are dealt round-robin to the 8 XCDs) and are dispatched back to back, so the second reader hits
-// that XCD's L2 and HBM is still read once.
-// Partial layout (n_split > 1): part_ml [units][n_split][RPT][2], part_o [units][n_split][RPT][D], RPT =
-// 32 * (query tiles of a unit).
+// A unit = (work item, KV head) is covered by q_blocks workgroups (NQ*QG query tiles each).  Workgroups of
+// different query blocks stream the same K/V; the one-dimensional grid is decoded so that all workgroups of a
+// unit run on the same XCD (ids are dealt round-robin to the 8 XCDs) and are dispatched back to back, so the
+// second reader hits that XCD's L2 and HBM is still read once.
+// Partials (sequences with several chunks): part_ml [item][Hkv][RPT][2], part_o [item][Hkv][RPT][D], RPT =
+// 32 * (query tiles of a unit); counters [sequence][Hkv][q_blocks], zero between launches; queue [8]: next
+// position of every XCD's queue, zeroed by the plan kernel for every layer of the step.
+// The read-only index arrays arrive as separate __restrict__ arguments (not inside the by-value Plan / KvView
+// structs): only then can the compiler prove that the kernel's own stores never alias them, and only then do the
+// per-tile block-table lookups stay scalar loads inside the persistent loop.  A vector load of a page id in the
+// tile loop must be waited for with vmcnt(0), which serialises the K/V prefetch.
 template <int NQ, int QG, int D>
-__global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B, int Hq, int Hkv, float scale_log2e,
+__global__ void __launch_bounds__(256) attn_mfma_kernel(const int32_t* __restrict__ seq_k, const int32_t* __restrict__ seq_c,
+                                                        const int32_t* __restrict__ row_start, const int32_t* __restrict__ seq_slot,
+                                                        const int32_t* __restrict__ attn_meta, const int32_t* __restrict__ item_start,
+                                                        const int32_t* __restrict__ item_seq, const int32_t* __restrict__ item_chunk,
+                                                        const int32_t* __restrict__ block_table, int max_pages, int n_pages,
+                                                        int n_units, int Hq, int Hkv, float scale_log2e,
                                                         const f16* __restrict__ q, const f16* __restrict__ k_pages,
                                                         const f16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
-                                                        int n_split, int q_blocks) {
+                                                        int32_t* __restrict__ counters, int32_t* __restrict__ queue,
+                                                        int q_blocks) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product
   constexpr int DT = D / 32;            // 32-wide d tiles of the output
   constexpr int RP = 32 * NQ * QG;      // padded query rows per workgroup
@@ -60,17 +74,29 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
   constexpr int ROWS_W = 32 * NQ;       // query rows held by one wave
   constexpr int LDO = D + 4;            // row stride (floats) of an accumulator in LDS: 4 banks of skew per row
   extern __shared__ __align__(16) char lds_raw[];
+  constexpr int kListMax = 64;          // units with partials waiting for the next flush
+  __shared__ int s_list[kListMax];
+  __shared__ int s_nlist;
+  __shared__ int s_w;
 
-  const int zdim = n_split * q_blocks;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int z = slot % zdim, unit = (slot / zdim) * 8 + xcd;
-  if (unit >= B * Hkv) return;
-  const int h = unit % Hkv, b = unit / Hkv, split = z % n_split;
-  const int qt0 = (z / n_split) * NQ * QG;              // first query tile of this workgroup
-  const int k = p.seq_k[b];
+  // Persistent workgroups with one work queue per XCD.  Unit u belongs to XCD u % 8 (workgroup ids are dealt
+  // round-robin to the XCDs), and that XCD's queue lists (unit, query block) pairs with the query blocks of a
+  // unit next to each other, so they are picked up by workgroups of the same XCD at about the same time and the
+  // second reader of the unit's K/V hits L2.  A workgroup starts with the pair at its own position and then
+  // takes pairs from the queue (one atomic each) until none is left: units differ in cost (chunk tails, number
+  // of draft rows), a static assignment left a quarter of the GPU idle on ragged batches.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, wgs_per_xcd = gridDim.x >> 3;
+  const int n_live = min(attn_meta[1] * Hkv, n_units);
+  const int total_w = (n_live > xcd ? (n_live - xcd + 7) / 8 : 0) * q_blocks;   // pairs of this XCD
+  auto process = [&](const int unit, const int qb) {
+  const int item = unit / Hkv, h = unit % Hkv;
+  const int b = item_seq[item], chunk = item_chunk[item];
+  const int n_ch = item_start[b + 1] - item_start[b];   // chunks of this sequence
+  const int qt0 = qb * NQ * QG;                         // first query tile of this workgroup
+  const int k = seq_k[b];
   if (k < 0) return;
   const int G = Hq / Hkv;
-  const int c = p.seq_c[b];
+  const int c = seq_c[b];
   const int n_tok = c + k + 1;
   const int R = (k + 1) * G;
   if (qt0 * 32 >= R) return;                            // this sequence has fewer query rows
@@ -80,8 +106,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int grp = wave / WPG, wig = wave % WPG;
   const int ln = lane & 31, lg = lane >> 5;
-  const int row0 = p.row_start[b];
-  const int32_t* bt = kv.block_table + (size_t)p.seq_slot[b] * kv.max_pages;
+  const int row0 = row_start[b];
+  const int32_t* __restrict__ bt = block_table + (size_t)seq_slot[b] * max_pages;
   const size_t page_elems = kv_page_elems(Hkv, D);
 
   // Query fragments (B operand: lane (n, g) holds Q[row n][g*D/2 + 8s + j]) are staged once in LDS in
@@ -95,8 +121,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
     lim[qt] = (qr < R) ? c + qr / G : -1;
   }
   const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int tps = (n_tiles + n_split - 1) / n_split;
-  const int t_begin = split * tps, t_end = min(t_begin + tps, n_tiles);
+  const int cht = attn_meta[0];
+  const int t_begin = min(chunk * cht, n_tiles), t_end = min(t_begin + cht, n_tiles);
   const bool group_active = ((qt0 + grp * NQ) * 32) < R;        // wave-uniform
   // tiles of this wave: t0, t0 + WPG, ... (n_my of them)
   const int t0 = t_begin + wig;
@@ -104,7 +130,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
   const int t_last = t0 + (n_my - 1) * WPG;
   auto tile_offset = [&](int t) -> size_t {
     const int tb = t * kTile;
-    const int page = min(max(bt[tb / kPage], 0), kv.n_pages - 1);
+    const int page = min(max(bt[tb / kPage], 0), n_pages - 1);
     return (size_t)page * page_elems + (size_t)(h * 2 + ((tb / kTile) & 1)) * (kTile * D) + lane * 8;
   };
   auto load_k = [&](size_t off, u32x4 (&kf)[KS]) {
@@ -249,7 +275,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
   // Every wave stores its unscaled accumulator (rows x D, row-major, padded rows) and its per-row
   // (max, sum) in LDS; after ONE barrier all 256 threads combine them: TPR threads per query row, each
   // sums its 16-byte chunks over the waves of the row's group with the usual exp2(m_w - m) weights and
-  // writes the result (final rows: normalised float16; KV splits: float32 partial + (m, l)).
+  // writes the result (single chunk: normalised float16 rows; several chunks: float32 partial + (m, l)).
   float* s_o = (float*)lds_raw;                         // [4 waves][ROWS_W][LDO]
   float* s_m = s_o + 4 * ROWS_W * LDO;                  // [4][ROWS_W] per-wave running max
   float* s_l = s_m + 4 * ROWS_W;                        // [4][ROWS_W] per-wave sum
@@ -294,7 +320,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
       const int iq = qr / G, hg = qr % G;
       const float inv = 1.0f / lt;                      // row i always sees at least position c + i: lt > 0
       f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
-      const size_t pr = ((size_t)unit * n_split + split) * ((size_t)RP * q_blocks) + qr;
+      const size_t pr = (size_t)unit * ((size_t)RP * q_blocks) + qr;
 #pragma unroll
       for (int j = 0; j < CH / TPR; ++j) {
         const int ch = sub + j * TPR;
@@ -305,7 +331,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[e] += v[e] * mw[w];
         }
-        if (n_split == 1) {
+        if (n_ch == 1) {
           typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
           f16x4 v;
 #pragma unroll
@@ -315,34 +341,97 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(Plan p, KvView kv, int B
           *(f32x4*)(part_o + pr * D + ch * 4) = acc;
         }
       }
-      if (n_split > 1 && sub == 0) { part_ml[pr * 2] = mt; part_ml[pr * 2 + 1] = lt; }
+      if (n_ch > 1 && sub == 0) { part_ml[pr * 2] = mt; part_ml[pr * 2 + 1] = lt; }
     }
+    // several chunks: remember the unit; its partial is published and merged in flush() below
+    if (n_ch > 1 && threadIdx.x == 0) { s_list[s_nlist] = unit * q_blocks + qb; s_nlist = s_nlist + 1; }
   }
-}
+  };   // process
 
-// Combines the KV splits of one (packed row, query head): standard log-sum-exp merge.
-template <int D>
-__global__ void __launch_bounds__(D) attn_merge_kernel(Plan p, int Hq, int Hkv, int RP, const float* __restrict__ part_o,
-                                                       const float* __restrict__ part_ml, int n_split,
-                                                       f16* __restrict__ out) {
-  const int r = blockIdx.x, hq = blockIdx.y;
-  if (r >= p.n_rows[0]) return;
-  const int b = p.row_seq[r], iq = p.row_pos[r];
-  const int G = Hq / Hkv, h = hq / G, hg = hq % G;
-  const int qr = iq * G + hg;
-  const size_t base = (((size_t)b * Hkv + h) * n_split) * RP + qr;   // RP: padded query rows of a unit
-  float mt = -INFINITY;
-  for (int s = 0; s < n_split; ++s) mt = fmaxf(mt, part_ml[(base + (size_t)s * RP) * 2]);
-  float lt = 0.f, acc = 0.f;
-  for (int s = 0; s < n_split; ++s) {
-    const size_t pr = base + (size_t)s * RP;
-    const float m = part_ml[pr * 2];
-    if (m == -INFINITY) continue;
-    const float f = exp2f(m - mt);
-    lt += part_ml[pr * 2 + 1] * f;
-    acc += part_o[pr * D + threadIdx.x] * f;
+  // Merge of the units with several chunks: the LAST workgroup of (sequence, KV head, query block) to publish
+  // its partial merges all of them; nobody waits.  Release: the workgroup's partial stores are made visible
+  // device-wide (one fence for all units in the list: a fence per unit, i.e. an L2 write-back and invalidate
+  // each, cost more than the attention itself on ragged batches) before the counters are bumped; acquire: a
+  // workgroup that reads n_ch - 1 sees the partials of all the others.
+  auto merge_unit = [&](const int unit, const int qb) {
+    const int item = unit / Hkv, h = unit % Hkv;
+    const int b = item_seq[item];
+    const int n_ch = item_start[b + 1] - item_start[b];
+    const int G = Hq / Hkv, R = (seq_k[b] + 1) * G, row0 = row_start[b];
+    constexpr int TPR = 256 / RP, CH = D / 4;
+    const int wr = threadIdx.x / TPR, sub = threadIdx.x % TPR;
+    const int qr = qb * RP + wr;
+    if (qr >= R) return;
+    const size_t rpt = (size_t)RP * q_blocks;
+    const size_t u0 = (size_t)item_start[b] * Hkv + h;           // unit of chunk 0; chunk c is Hkv units further
+    float mt = -INFINITY;
+    for (int c = 0; c < n_ch; ++c) mt = fmaxf(mt, part_ml[((u0 + (size_t)c * Hkv) * rpt + qr) * 2]);
+    float lt = 0.f;
+    f32x4 acc[CH / TPR];
+#pragma unroll
+    for (int j = 0; j < CH / TPR; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < n_ch; ++c) {
+      const size_t pc = (u0 + (size_t)c * Hkv) * rpt + qr;
+      const float m = part_ml[pc * 2];
+      if (m == -INFINITY) continue;
+      const float f = __builtin_amdgcn_exp2f(m - mt);
+      lt += part_ml[pc * 2 + 1] * f;
+#pragma unroll
+      for (int j = 0; j < CH / TPR; ++j) {
+        const f32x4 v = *(const f32x4*)(part_o + pc * D + (sub + j * TPR) * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] += v[e] * f;
+      }
+    }
+    const int iq = qr / G, hg = qr % G;
+    const float inv = 1.0f / lt;
+    f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
+#pragma unroll
+    for (int j = 0; j < CH / TPR; ++j) {
+      typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+      f16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (f16)(acc[j][e] * inv);
+      *(f16x4*)(dst + (sub + j * TPR) * 4) = v;
+    }
+  };
+  auto flush = [&]() {
+    __syncthreads();
+    const int n = s_nlist;
+    if (n == 0) return;                                 // uniform
+    __threadfence();
+    __syncthreads();
+    if ((int)threadIdx.x < n) {
+      const int unit = s_list[threadIdx.x] / q_blocks, qb = s_list[threadIdx.x] % q_blocks;
+      const int item = unit / Hkv, h = unit % Hkv, b = item_seq[item];
+      const int n_ch = item_start[b + 1] - item_start[b];
+      int32_t* cnt = counters + ((size_t)b * Hkv + h) * q_blocks + qb;
+      const int old = atomicAdd(cnt, 1);
+      const bool last = old == n_ch - 1;
+      if (last) *cnt = 0;                               // ready for the next launch (stream order)
+      else s_list[threadIdx.x] = -1;
+    }
+    __syncthreads();
+    __threadfence();
+    for (int i = 0; i < n; ++i)
+      if (s_list[i] >= 0) merge_unit(s_list[i] / q_blocks, s_list[i] % q_blocks);
+    __syncthreads();
+    if (threadIdx.x == 0) s_nlist = 0;
+  };
+
+  if (threadIdx.x == 0) s_nlist = 0;
+  int w = slot;                                         // position in this XCD's queue
+  while (w < total_w) {
+    __syncthreads();                                    // LDS of the previous unit is no longer read
+    if (s_nlist == kListMax) flush();
+    process(xcd + 8 * (w / q_blocks), w % q_blocks);
+    if (total_w <= wgs_per_xcd) break;                  // at most one pair per workgroup: nothing to take
+    __syncthreads();
+    if (threadIdx.x == 0) s_w = atomicAdd(queue + xcd, 1) + wgs_per_xcd;
+    __syncthreads();
+    w = __builtin_amdgcn_readfirstlane(s_w);         // keeps everything derived from it on the scalar unit
   }
-  out[(size_t)r * Hq * D + (size_t)hq * D + threadIdx.x] = (f16)(acc / lt);
+  flush();
 }
 
 static int rows_padded(const Shape& s, int k_max) {
@@ -352,50 +441,100 @@ static int rows_padded(const Shape& s, int k_max) {
   return 128;
 }
 
+// Scratch: completion counters [B_max][Hkv][4], then (max, sum) and float32 partial rows of every unit
+// (work item x KV head) at the largest work-list capacity.
+static size_t counters_bytes(const Shape& s, int B_max) { return ((size_t)B_max * s.Hkv * 4 * sizeof(int32_t) + 255) / 256 * 256; }
+
 size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max) {
   if (s.dtype != BS_BF16) return 256;
-  size_t rp = rows_padded(s, k_max);
-  return (size_t)B_max * s.Hkv * kMaxSplit * rp * (s.D + 2) * sizeof(float);
+  const size_t rp = rows_padded(s, k_max);
+  const size_t units = (size_t)attn_item_capacity(B_max, kAttnMaxSmin) * s.Hkv;
+  return counters_bytes(s, B_max) + units * rp * (s.D + 2) * sizeof(float);
+}
+
+// Test hook, not part of the public ABI: forces the launch shape of the bf16 attention kernel (0 = choose
+// automatically) so that every instantiation can be exercised at small batch sizes: q_blocks = query blocks
+// per (sequence, KV head) (ignored if it does not divide the number of query tiles), n_chunks = token chunks
+// of the longest sequence.
+static int g_force_q_blocks = 0, g_force_n_chunks = 0;
+extern "C" void bs_debug_attention_shape(int q_blocks, int n_chunks) {
+  g_force_q_blocks = q_blocks;
+  g_force_n_chunks = n_chunks;
+}
+
+// Shape of the launch.  A unit = (sequence, KV head) has `tiles` query tiles of 32 rows.  With enough units to
+// fill the 256 CUs one workgroup takes all tiles of a unit (K/V fragments are loaded once and used for every
+// tile); with fewer units the query tiles are spread over q_blocks workgroups (the extra readers hit L2).  What
+// is still missing to reach ~256 workgroups, and the balance between sequences of different length, comes from
+// the token chunks of the work list, which the plan kernel sizes on the device from s_min = wanted (sequence,
+// chunk) items.
+static void launch_shape(const Shape& s, int B, int k_max, int& q_blocks, int& s_min, int& force_chunks) {
+  static const char* split_env = getenv("BS_ATTN_SPLIT");          // tuning aids
+  static const char* qb_env = getenv("BS_ATTN_QBLOCKS");
+  const int tiles = rows_padded(s, k_max) / 32;                    // 1, 2 or 4
+  const int units = B * s.Hkv;
+  q_blocks = 1;
+  if (tiles == 2 && units < 256) q_blocks = 2;
+  // four tiles: two query blocks of two tiles each.  One workgroup per unit (two wave groups of two tiles) leaves
+  // the second group, half of the CU, idle for every sequence with few draft rows; four blocks of one tile
+  // stream every K/V tile through L2 four times (measured, 7B heads: 4 sequences of 60k tokens 137 us with two
+  // blocks against 196 us with four; ragged batch of 128: 627 us against 729 us).
+  if (tiles == 4) q_blocks = 2;
+  const int qb_forced = g_force_q_blocks ? g_force_q_blocks : (qb_env ? atoi(qb_env) : 0);
+  if (qb_forced >= 1 && qb_forced <= tiles && tiles % qb_forced == 0) q_blocks = qb_forced;
+  s_min = (256 + s.Hkv * q_blocks - 1) / (s.Hkv * q_blocks);
+  if (s_min > kAttnMaxSmin) s_min = kAttnMaxSmin;
+  force_chunks = g_force_n_chunks ? g_force_n_chunks : (split_env ? atoi(split_env) : 0);
+}
+
+void attention_plan_params(const Shape& s, int B, int k_max, int* s_min, int* force_chunks) {
+  if (s.dtype != BS_BF16) { *s_min = 0; *force_chunks = 0; return; }
+  int q_blocks;
+  launch_shape(s, B, k_max, q_blocks, *s_min, *force_chunks);
+}
+
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+void launch_attention_init(const Shape& s, int B_max, void* scratch, hipStream_t st) {
+  if (s.dtype != BS_BF16) return;
+  const int n = (int)(counters_bytes(s, B_max) / sizeof(int32_t));
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (int32_t*)scratch, n);
 }
 
 template <int NQ, int QG, int D>
-static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int B, int M_max, const void* q,
-                             const void* k_pages, const void* v_pages, void* out, void* scratch, int n_split,
-                             int q_blocks, void* prof_token, hipStream_t st) {
+static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, int layer, int B, int B_max, int M_max, const void* q,
+                             const void* k_pages, const void* v_pages, void* out, void* scratch, int q_blocks,
+                             int s_min, void* prof_token, hipStream_t st) {
   constexpr int RP = 32 * NQ * QG;
   const int rpt = RP * q_blocks;                                       // padded query rows of a unit
   size_t lds = (size_t)4 * 32 * NQ * (D + 4) * 4 + 2 * 4 * 32 * NQ * 4;   // accumulators of 4 waves + statistics
   const size_t lds_q = (size_t)(RP / 32) * (D / 16) * 1024;           // query fragments (same region, earlier)
   if (lds < lds_q) lds = lds_q;
-  float* part_ml = (float*)scratch;
-  float* part_o = part_ml + (size_t)B * s.Hkv * n_split * rpt * 2;
+  const int n_units = attn_item_capacity(B, s_min) * s.Hkv;
+  int32_t* counters = (int32_t*)scratch;
+  float* part_ml = (float*)((char*)scratch + counters_bytes(s, B_max));
+  float* part_o = part_ml + (size_t)n_units * rpt * 2;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   auto kern = attn_mfma_kernel<NQ, QG, D>;
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
-  const int units = B * s.Hkv;
-  const int grid = (units + 7) / 8 * 8 * n_split * q_blocks;
+  // one workgroup per CU (every instantiation for head size 128 needs more than half of a CU's registers);
+  // fewer when the work list cannot be longer
+  const int cap_w = (n_units * q_blocks + 7) / 8 * 8;
+  const int grid = cap_w < 256 ? cap_w : 256;
   if (prof_token) attention_prof_mark(prof_token, st, true);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p, kv, B, s.Hq, s.Hkv, scale_log2e, (const f16*)q,
-                     (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, n_split, q_blocks);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p.seq_k, p.seq_c, p.row_start, p.seq_slot, p.attn_meta,
+                     p.item_start, p.item_seq, p.item_chunk, kv.block_table, kv.max_pages, kv.n_pages, n_units, s.Hq,
+                     s.Hkv, scale_log2e, (const f16*)q,
+                     (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, counters, p.attn_queue + 8 * layer, q_blocks);
   if (prof_token) attention_prof_mark(prof_token, st, false);
-  if (n_split > 1)
-    hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(M_max, s.Hq), dim3(D), 0, st, p, s.Hq, s.Hkv, rpt, part_o, part_ml,
-                       n_split, (f16*)out);
 }
 
-// Test hook, not part of the public ABI: forces the launch shape of the bf16 attention kernel (0 = choose
-// automatically) so that every instantiation can be exercised at small batch sizes.  A q_blocks value that
-// does not divide the number of query tiles is ignored.
-static int g_force_q_blocks = 0, g_force_n_split = 0;
-extern "C" void bs_debug_attention_shape(int q_blocks, int n_split) {
-  g_force_q_blocks = q_blocks;
-  g_force_n_split = n_split;
-}
-
-void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
-                      const void* k_pages, const void* v_pages, void* out, void* scratch, void* prof_token,
-                      hipStream_t st) {
+void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int layer, int B, int B_max, int k_max, int M_max,
+                      const void* q, const void* k_pages, const void* v_pages, void* out, void* scratch,
+                      void* prof_token, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)s.D);
   static const bool force_simple = getenv("BS_SIMPLE_ATTN") != nullptr;   // debugging aid
   if (s.dtype == BS_F32) {
@@ -408,28 +547,13 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, in
                        (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out);
     return;
   }
-  // Shape of the launch.  A unit = (sequence, KV head) has `tiles` query tiles of 32 rows.  With enough
-  // units to fill the 256 CUs one workgroup takes all tiles of a unit (K/V fragments are loaded once and
-  // used for every tile); with fewer units the query tiles are spread over q_blocks workgroups (the extra
-  // readers hit L2), and what is still missing to reach ~256 workgroups comes from splitting the token
-  // range (n_split, which costs a merge kernel).
-  static const char* split_env = getenv("BS_ATTN_SPLIT");          // tuning aids
-  static const char* qb_env = getenv("BS_ATTN_QBLOCKS");
-  const int tiles = rows_padded(s, k_max) / 32;                    // 1, 2 or 4
-  const int units = B * s.Hkv;
-  int q_blocks = 1;
-  if (tiles == 2 && units < 256) q_blocks = 2;
-  if (tiles == 4) q_blocks = units < 128 ? 4 : (units < 256 ? 2 : 1);
-  const int qb_forced = g_force_q_blocks ? g_force_q_blocks : (qb_env ? atoi(qb_env) : 0);
-  if (qb_forced >= 1 && qb_forced <= tiles && tiles % qb_forced == 0) q_blocks = qb_forced;
-  const int wgs = units * q_blocks;
-  int n_split = g_force_n_split ? g_force_n_split : (split_env ? atoi(split_env) : (256 + wgs / 2) / wgs);   // ~ one workgroup per CU
-  n_split = n_split < 1 ? 1 : (n_split > kMaxSplit ? kMaxSplit : n_split);
-  const int tiles_wg = tiles / q_blocks;                           // query tiles per workgroup: 1, 2 or 4
+  int q_blocks, s_min, force_chunks;
+  launch_shape(s, B, k_max, q_blocks, s_min, force_chunks);
+  const int tiles_wg = rows_padded(s, k_max) / 32 / q_blocks;      // query tiles per workgroup: 1, 2 or 4
 #define BS_ATTN(NQ, QG)                                                                                         \
   do {                                                                                                          \
-    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, q_blocks, prof_token, st); \
-    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, B, M_max, q, k_pages, v_pages, out, scratch, n_split, q_blocks, prof_token, st);   \
+    if (s.D == 128) launch_mfma_attn<NQ, QG, 128>(s, p, kv, layer, B, B_max, M_max, q, k_pages, v_pages, out, scratch, q_blocks, s_min, prof_token, st); \
+    else launch_mfma_attn<NQ, QG, 64>(s, p, kv, layer, B, B_max, M_max, q, k_pages, v_pages, out, scratch, q_blocks, s_min, prof_token, st);   \
   } while (0)
   if (tiles_wg == 1) BS_ATTN(1, 1);
   else if (tiles_wg == 2) BS_ATTN(2, 1);

@@ -79,7 +79,20 @@ struct Plan {
   int32_t* row_pos;     // [M_max] i in 0..k_b
   int32_t* row_tok;     // [M_max] input token of row r
   int32_t* row_target;  // [M_max] draft token judged by row r (-1: none)
+  // attention work list (bf16 models): every sequence's token range is cut into chunks of chunk_tiles 32-token
+  // tiles; item i = (sequence item_seq[i], chunk item_chunk[i]); the items of sequence b are
+  // item_start[b] .. item_start[b+1]-1
+  int32_t* attn_meta;   // [2]   chunk_tiles, number of items
+  int32_t* item_start;  // [B+1]
+  int32_t* item_seq;    // [item capacity]
+  int32_t* item_chunk;  // [item capacity]
+  int32_t* attn_queue;  // [n_layers][8] next position of every XCD's work queue (zeroed by plan_kernel)
 };
+
+// Capacity of the attention work list for B sequences when the launch wants at least s_min (sequence, chunk)
+// items (see plan_kernel): sum_b chunks(b) <= B + S with S <= 4 max(B, s_min).
+__host__ __device__ __forceinline__ int attn_item_capacity(int B, int s_min) { return 5 * (B > s_min ? B : s_min); }
+constexpr int kAttnMaxSmin = 256;
 
 struct KvView {
   int n_pages, n_slots, max_pages;
@@ -95,9 +108,11 @@ struct Shape {
 
 // ---- launchers (each .hip file defines its own kernels and these host wrappers) ---------------
 // plan.hip
+// attn_s_min > 0: also build the attention work list (wanted number of items, at most kAttnMaxSmin);
+// attn_force_chunks > 0 (tests): chunk size such that the longest sequence has that many chunks.
 void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, const int32_t* seq_slot,
                  const int32_t* last_token, const int32_t* draft_tokens, const int32_t* draft_len,
-                 bool need_kv, hipStream_t st);
+                 bool need_kv, int attn_s_min, int attn_force_chunks, int n_layers, hipStream_t st);
 void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot,
                    const int32_t* n_commit, hipStream_t st);
 void launch_clear_status(int32_t* status, hipStream_t st);
@@ -134,9 +149,13 @@ int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_ma
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st);
 // attention.hip
-void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int B, int k_max, int M_max, const void* q,
-                      const void* k_pages, const void* v_pages, void* out, void* scratch, void* prof_token,
-                      hipStream_t st);
+// attention_plan_params gives the work-list parameters launch_plan needs for the same (B, k_max);
+// launch_attention_init clears the completion counters once, at context creation.
+void attention_plan_params(const Shape& s, int B, int k_max, int* s_min, int* force_chunks);
+void launch_attention_init(const Shape& s, int B_max, void* scratch, hipStream_t st);
+void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int layer, int B, int B_max, int k_max, int M_max,
+                      const void* q, const void* k_pages, const void* v_pages, void* out, void* scratch,
+                      void* prof_token, hipStream_t st);
 void attention_prof_mark(void* token, hipStream_t st, bool begin);   // api.hip: event pair around the main kernel
 size_t attention_scratch_bytes(const Shape& s, int B_max, int k_max);
 // sampler.hip

@@ -9,7 +9,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
                                                    const int32_t* __restrict__ seq_slot,
                                                    const int32_t* __restrict__ last_token,
                                                    const int32_t* __restrict__ draft_tokens,
-                                                   const int32_t* __restrict__ draft_len, int need_kv) {
+                                                   const int32_t* __restrict__ draft_len, int need_kv, int attn_s_min,
+                                                   int attn_force_chunks, int n_layers) {
   __shared__ int s_fault;
   __shared__ int s_slot[4096];                      // B <= 4096 (checked at context creation)
   __shared__ int s_k[4096];                         // validated k_b (-1: skipped)
@@ -102,6 +103,63 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   }
   __syncthreads();
   if (tid == 0 && s_fault) atomicOr(p.status, s_fault);
+  if (!need_kv || attn_s_min <= 0) return;
+  for (int i = tid; i < 8 * n_layers; i += blockDim.x) p.attn_queue[i] = 0;
+
+  // phase 4: attention work list.  The (sequence, KV head) streams of a ragged batch differ in length by
+  // orders of magnitude (contexts of 512 .. 32768 tokens in one step), so the token range of every sequence
+  // is cut into chunks of a common size; the attention kernel's persistent workgroups walk the (sequence,
+  // chunk) items.  T = tiles in total, S0 = max(B, s_min) = items that fill the GPU once:
+  //   * lengths within 25 % of their mean: chunk = ceil(1.25 T / S0) if S0 = B (one chunk per sequence: no
+  //     partial results), ceil(T / S0) if the batch is smaller than s_min (equal chunks, one round);
+  //   * ragged batch: chunk = ceil(T / 4 S0), four items per workgroup lane, so the lanes end together.
+  // sum_b chunks(b) <= B + T / chunk <= B + 4 S0 always (the work list's capacity).
+  __shared__ int s_red[256];
+  __shared__ int s_cht;
+  auto tiles_of = [&](int b) { return s_k[b] < 0 ? 0 : (p.seq_c[b] + s_k[b] + 1 + kTile - 1) / kTile; };
+  {
+    int t = 0, mx = 0, nv = 0;
+    for (int b = b_lo; b < b_hi; ++b) { const int n = tiles_of(b); t += n; mx = max(mx, n); nv += n > 0; }
+    s_pr[tid] = t; s_red[tid] = mx; s_pt[tid] = nv;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    long long T = 0; int mx = 0; long long s_valid = 0;
+    for (int i = 0; i < 256; ++i) { T += s_pr[i]; mx = max(mx, s_red[i]); s_valid += s_pt[i]; }
+    const int S = max(B, attn_s_min), cap = attn_item_capacity(B, attn_s_min);
+    long long cht = (S > B) ? (T + S - 1) / S : (5 * T + 4LL * S - 1) / (4LL * S);
+    if (4LL * mx * s_valid > 5 * T) cht = (T + 4LL * S - 1) / (4LL * S);       // ragged: longest > 1.25 x mean
+    if (attn_force_chunks > 0) cht = (mx + attn_force_chunks - 1) / attn_force_chunks;
+    const long long floor_cht = (T + (cap - B) - 1) / (cap - B);      // keeps sum_b ceil(n_b / cht) <= cap
+    if (cht < floor_cht) cht = floor_cht;
+    if (cht < 1) cht = 1;
+    s_cht = (int)min(cht, (long long)0x3fffffff);
+  }
+  __syncthreads();
+  const int cht = s_cht;
+  {
+    int n = 0;
+    for (int b = b_lo; b < b_hi; ++b) n += (tiles_of(b) + cht - 1) / cht;
+    s_pr[tid] = n;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int n = 0;
+    for (int i = 0; i < 256; ++i) { const int a = s_pr[i]; s_pr[i] = n; n += a; }
+    p.item_start[B] = n;
+    p.attn_meta[0] = cht;
+    p.attn_meta[1] = n;
+  }
+  __syncthreads();
+  {
+    int n = s_pr[tid];
+    for (int b = b_lo; b < b_hi; ++b) {
+      p.item_start[b] = n;
+      const int nc = (tiles_of(b) + cht - 1) / cht;
+      for (int c = 0; c < nc; ++c) { p.item_seq[n + c] = b; p.item_chunk[n + c] = c; }
+      n += nc;
+    }
+  }
 }
 
 __global__ void commit_kernel(Plan p, KvView kv, int B, const int32_t* __restrict__ seq_slot,
@@ -119,9 +177,9 @@ __global__ void clear_status_kernel(int32_t* status) { *status = 0; }
 
 void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, const int32_t* seq_slot,
                  const int32_t* last_token, const int32_t* draft_tokens, const int32_t* draft_len,
-                 bool need_kv, hipStream_t st) {
+                 bool need_kv, int attn_s_min, int attn_force_chunks, int n_layers, hipStream_t st) {
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, p, kv, B, k_max, vocab, seq_slot, last_token,
-                     draft_tokens, draft_len, need_kv ? 1 : 0);
+                     draft_tokens, draft_len, need_kv ? 1 : 0, attn_s_min, attn_force_chunks, n_layers);
 }
 void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot, const int32_t* n_commit,
                    hipStream_t st) {

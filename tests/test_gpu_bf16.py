@@ -126,6 +126,18 @@ def test_mini_maximum_draft_length():
     _run_case(desc, ctx_lens=[90, 3, 500, 64], k_b=[30, 0, 17, 29], k_max=30, seed=33)
 
 
+def test_mini_many_ragged_sequences():
+    """40 sequences with contexts from 0 to 900 tokens and 0..8 drafts: the attention work list cuts them into
+    several hundred chunks, more than there are workgroups, so the per-XCD work queues, the partial results and
+    the last-arriver merge are all exercised."""
+    desc = W.shape("mini_bf16")
+    rng = np.random.default_rng(35)
+    ctx = [int(x) for x in rng.integers(0, 900, 40)]
+    ctx[3], ctx[17] = 0, 899
+    k_b = [int(x) for x in rng.integers(0, 9, 40)]
+    _run_case(desc, ctx_lens=ctx, k_b=k_b, k_max=8, seed=35, check_kv=False)
+
+
 def test_mini_head_dim_64():
     desc = W.shape("mini_bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, vocab=4096)
     _run_case(desc, ctx_lens=[100, 513, 64], k_b=[3, 8, 8], k_max=8, seed=25)
@@ -135,7 +147,7 @@ def test_mini_head_dim_64():
 def test_attention_launch_shapes_k16(q_blocks, n_split):
     """The G = 7, k = 16 case (four query tiles per KV head) under every launch shape of the attention kernel:
     one workgroup per unit with two wave groups (1 query block), two tiles per workgroup (2) and one tile per
-    workgroup (4), each with and without a KV split."""
+    workgroup (4), each with one token chunk per sequence and with the longest sequence cut into several."""
     desc = W.shape("mini_bf16", n_q_heads=14, n_kv_heads=2, d_model=320, d_ffn=448, vocab=777)
     B.bs_debug_attention_shape(q_blocks, n_split)
     try:
