@@ -170,8 +170,10 @@ def main():
         "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "s1p5b_b%d_c%d_k%d (BASELINE configs[1]: 1.5B-shape bf16 decoder, %d layers, dense q, "
-                               "agreement 0.7)" % (args.batch, args.context, args.k, args.layers),
+        "config": {"workload": "s1p5b_b%d_c%d_k%d (%s1.5B-shape bf16 decoder, %d layers, dense q, agreement 0.7)"
+                               % (args.batch, args.context, args.k,
+                                  "BASELINE configs[1]: " if (args.batch, args.context, args.k, args.layers) == (64, 2048, 8, 28)
+                                  else "NOT the headline configuration: ", args.layers),
                    "batch": args.batch, "context": args.context, "k": args.k},
         "accepted_draft_tokens_per_s": accepted / dt,
         "emitted_per_seq_per_step": emitted / (args.steps * args.batch),
