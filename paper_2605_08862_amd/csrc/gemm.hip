@@ -222,6 +222,8 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   int total = m_blocks * n_blocks;
   int xps = 8 / n_split;                                   // n_split is 1, 2, 4 or 8
   int grid = 8 * ((total + xps - 1) / xps);
+  static bool attr_set = false;              // more than 64 KiB of dynamic LDS needs an opt-in (192-row tiles)
+  if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
                      N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split);
 }

@@ -54,7 +54,7 @@ template <int MT, int NT, bool SWAP>
 struct MfmaGemm {
   static constexpr int BM = 32 * MT;
   static constexpr int LDS_STAGE_BYTES = MT * 4 * 1024;        // MT row tiles x 4 K-steps x 1 KiB
-  static constexpr int LDS_BYTES = 2 * LDS_STAGE_BYTES;
+  static constexpr int LDS_BYTES = 3 * LDS_STAGE_BYTES;        // three stages: see body()
 
   // Chunk assignment of thread t for the activation tile: chunk q = i*256 + t is the q%8-th 16-byte
   // piece of row q/8, i.e. (g, s) = (q%8 / 4, q%4): eight consecutive lanes read one full 128-byte line
@@ -98,9 +98,9 @@ struct MfmaGemm {
     for (int i = 0; i < MT; ++i) xreg[STAGE][i] = *(const u32x4*)(op.x_rows[i] + (size_t)kt * kBK);
   }
 
-  // One K tile.  STAGE = (kt - kt0) % 3 names the register ring slots: weights of tile j live in
-  // wreg[j % 3], activation chunks of tile j in xreg[j % 3] until they are written to LDS stage j & 1.
-  // Both streams are requested two iterations before they are needed.
+  // One K tile.  STAGE = (kt - kt0) % 3 names the ring slots: weights of tile j live in wreg[j % 3], activation
+  // chunks of tile j in xreg[j % 3] until they are written to LDS stage j % 3.  Both streams are requested two
+  // iterations before they are needed.
   //
   // Issue order.  The MFMA pipe runs asynchronously, so the memory instructions of the iteration are
   // dealt out between the MFMA groups instead of being issued in one burst at the top (14 global loads
@@ -111,22 +111,31 @@ struct MfmaGemm {
   // (s, mi).  Every load and store is UNCONDITIONAL (tile indices are clamped to the last tile): a
   // prefetch issued under a condition makes the compiler's wait-count tracking assume it may be the
   // newest outstanding load, and the resulting vmcnt(0) waits serialise the ring.
+  //
+  // The barrier.  The next tile's activations are stored to LDS in the first slots; the workgroup barrier
+  // sits between K-steps 2 and 3, and the slots of K-step 3 already read the NEXT tile's step-0 fragments
+  // into the free half of xf.  An iteration therefore starts with its first operands in registers: with
+  // the barrier at the end of the iteration all four waves hit LDS at once right after it and the matrix
+  // unit idled for ~300 cycles per tile until the first fragments arrived.  A wave can now run up to one
+  // barrier ahead of the slowest one (storing tile kt+2 while that one still reads tile kt), hence three
+  // LDS stages.
   template <int STAGE>
   __device__ static __forceinline__ void body(f32x16 (&acc)[MT][NT], u32x4 (&wreg)[3][NT][4], u32x4 (&xreg)[3][MT],
-                                              const Operands& op, int kt, int kt1, char* lds) {
+                                              u32x4 (&xf)[2][MT], const Operands& op, int kt, int kt1, char* lds) {
     const int lane = threadIdx.x & 63;
     constexpr int SLOTS = 4 * MT, EXTRA = 2 * MT + 4 * NT;
-    const char* stage = lds + (kt & 1) * LDS_STAGE_BYTES;
-    char* nstage = lds + ((kt + 1) & 1) * LDS_STAGE_BYTES;
+    const char* stage = lds + STAGE * LDS_STAGE_BYTES;
+    char* nstage = lds + ((STAGE + 1) % 3) * LDS_STAGE_BYTES;
     const int kx = min(kt + 3, kt1 - 1), kw = min(kt + 2, kt1 - 1);
-    u32x4 xf[2][MT];
-#pragma unroll
-    for (int mi = 0; mi < MT; ++mi) xf[0][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, 0, lane));
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < SLOTS; ++j) {
       const int s = j / MT, mi = j % MT;
+      if (j == 3 * MT) {                      // every LDS store of this iteration was issued in an earlier slot
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (s < 3) xf[(s + 1) & 1][mi] = *(const u32x4*)(stage + frag_lds_offset(mi, s + 1, lane));
+      else       xf[0][mi] = *(const u32x4*)(nstage + frag_lds_offset(mi, 0, lane));
 #pragma unroll
       for (int e = j * EXTRA / SLOTS; e < (j + 1) * EXTRA / SLOTS; ++e) {
         if (e < MT) {
@@ -147,35 +156,38 @@ struct MfmaGemm {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
   }
 
-  // Accumulates K tiles [kt0, kt1) into acc.  All 256 threads of the workgroup must call it.
+  // Accumulates K tiles [kt0, kt1) into acc.  All 256 threads of the workgroup must call it.  On return the
+  // waves are NOT synchronised and LDS may still be read by a slower wave: a caller that reuses LDS puts a
+  // barrier first.
   __device__ static __forceinline__ void run(f32x16 (&acc)[MT][NT], const Operands& op, int kt0, int kt1, char* lds) {
     if (kt0 >= kt1) return;
+    const int lane = threadIdx.x & 63;
     u32x4 xreg[3][MT];
     u32x4 wreg[3][NT][4];
-    // ring slots are indexed relative to kt0, LDS stages by the absolute tile parity
+    u32x4 xf[2][MT];
     load_x<0>(xreg, op, kt0);
     load_w<0>(wreg, op, kt0);
     load_x<1>(xreg, op, min(kt0 + 1, kt1 - 1));
     load_w<1>(wreg, op, min(kt0 + 1, kt1 - 1));
     load_x<2>(xreg, op, min(kt0 + 2, kt1 - 1));
-    char* stage0 = lds + (kt0 & 1) * LDS_STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) *(u32x4*)(stage0 + op.x_lds[i]) = xreg[0][i];
+    for (int i = 0; i < MT; ++i) *(u32x4*)(lds + op.x_lds[i]) = xreg[0][i];
     __syncthreads();
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) xf[0][mi] = *(const u32x4*)(lds + frag_lds_offset(mi, 0, lane));
     // whole rounds of three tiles without side exits (keeps the register ring free of copies at the
     // back edge), then the one or two remaining tiles
     int kt = kt0;
     for (; kt + 3 <= kt1; kt += 3) {
-      body<0>(acc, wreg, xreg, op, kt, kt1, lds);
-      body<1>(acc, wreg, xreg, op, kt + 1, kt1, lds);
-      body<2>(acc, wreg, xreg, op, kt + 2, kt1, lds);
+      body<0>(acc, wreg, xreg, xf, op, kt, kt1, lds);
+      body<1>(acc, wreg, xreg, xf, op, kt + 1, kt1, lds);
+      body<2>(acc, wreg, xreg, xf, op, kt + 2, kt1, lds);
     }
     if (kt < kt1) {
-      body<0>(acc, wreg, xreg, op, kt, kt1, lds);
-      if (kt + 1 < kt1) body<1>(acc, wreg, xreg, op, kt + 1, kt1, lds);
+      body<0>(acc, wreg, xreg, xf, op, kt, kt1, lds);
+      if (kt + 1 < kt1) body<1>(acc, wreg, xreg, xf, op, kt + 1, kt1, lds);
     }
   }
 };

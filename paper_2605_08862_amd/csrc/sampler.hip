@@ -561,6 +561,8 @@ static void launch_lmhead_t(const Shape& s, const int32_t* n_rows_dev, int M_max
   using G = MfmaGemm<MT, kLmNT, true>;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (s.V + 4 * kLmVtile - 1) / (4 * kLmVtile);
   int grid = ((m_blocks * n_blocks + 7) / 8) * 8;
+  static bool attr_set = false;              // more than 64 KiB of dynamic LDS needs an opt-in (192-row tiles)
+  if (!attr_set) { (void)hipFuncSetAttribute((const void*)lmhead_kernel<MT, STATS>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((lmhead_kernel<MT, STATS>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, s.V, s.d,
                      (const f16*)hf, x_rows, (const f16*)lm_head, inv_temp, row_target, sb, store, m_blocks, n_blocks);
 }
