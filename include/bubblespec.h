@@ -127,13 +127,26 @@ const char* bs_last_error(const bs_ctx* ctx);
 bs_status bs_pool_bind(bs_ctx* ctx, int n_prompts, int n_rollouts, const int32_t* pool_tokens,
                        const int64_t* rollout_offsets, const int32_t* prompt_rollout_begin);
 
+/* Sec. 3.2: prebuilt draft index (the per-prompt suffix structure with occurrence counts).  bs_index_build
+ * runs on the HOST: all three arrays are host pointers with the layout of bs_pool_bind; it returns a
+ * library-owned, position-independent blob (*blob_out, *bytes_out; release with bs_index_free).  The caller
+ * copies the blob to device memory and binds both copies with bs_index_bind (the host copy is only read during
+ * the call, the device copy must stay valid while bound; NULL, NULL unbinds).  While an index is bound
+ * bs_draft_lookup walks it (O(max_match + k_max) dependent loads per sequence) instead of scanning the pool,
+ * and returns exactly the same drafts.  Errors: BS_EINVAL (null, negative token, inconsistent offsets, foreign
+ * blob), BS_ESHAPE (a prompt's pool beyond 2^29 tokens), BS_ECAPACITY (out of host memory). */
+bs_status bs_index_build(int n_prompts, const int32_t* pool_tokens /*host*/, const int64_t* rollout_offsets /*host*/,
+                         const int32_t* prompt_rollout_begin /*host*/, void** blob_out /*host*/, size_t* bytes_out);
+void bs_index_free(void* blob);
+bs_status bs_index_bind(bs_ctx* ctx, const void* blob_host, const void* blob_dev, size_t bytes);
+
 /* Sec. 3.2 / Alg. 1 "retrieve a draft block": for each sequence b, match the last m tokens of
  * its rollout (tail_tokens[b], newest last, entries < 0 are padding) against the pool of prompt
  * seq_prompt[b], m from max_match down to min_match, taking the first m that occurs; then walk
  * up to k_max continuation tokens, each time taking the token that follows the most occurrences
  * (ties: smaller id) and keeping only the occurrences it follows.  Occurrences never straddle
  * rollouts.  Output draft_len[b] in [0,k_max]; draft_tokens[b][i >= draft_len[b]] = -1.
- * All pointers dev.  Errors: BS_ESTATE (no pool bound), BS_ESHAPE (B > B_max, k_max > ctx k_max,
+ * All pointers dev.  Errors: BS_ESTATE (no pool or index bound), BS_ESHAPE (B > B_max, k_max > ctx k_max,
  * max_match outside [1,8], min_match outside [1,max_match]), BS_EINVAL (null). */
 bs_status bs_draft_lookup(bs_ctx* ctx, int B, const int32_t* seq_prompt /*[B]*/,
                           const int32_t* tail_tokens /*[B,max_match]*/, int max_match, int min_match,

@@ -18,7 +18,8 @@ STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", 
 
 EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs_pool_bind", "bs_draft_lookup",
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
-           "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end"]
+           "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end", "bs_index_build", "bs_index_free",
+           "bs_index_bind"]
 PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
                 "sample": 7, "lookup": 8, "empty": 9}
 
@@ -63,6 +64,10 @@ def lib():
         L.bs_last_error.argtypes = [vp]
         L.bs_last_error.restype = C.c_char_p
         L.bs_pool_bind.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.bs_index_build.argtypes = [i32, vp, vp, vp, C.POINTER(vp), C.POINTER(C.c_size_t)]
+        L.bs_index_free.argtypes = [vp]
+        L.bs_index_free.restype = None
+        L.bs_index_bind.argtypes = [vp, vp, vp, C.c_size_t]
         L.bs_draft_lookup.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.bs_verify_step.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp]
         L.bs_accept_resample.argtypes = [vp, i32, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -75,7 +80,7 @@ def lib():
         L.bs_profile_begin.argtypes = [vp, i32]
         L.bs_profile_end.argtypes = [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         for name in EXPORTS:
-            if name not in ("bs_workspace_bytes", "bs_destroy", "bs_last_error"):
+            if name not in ("bs_workspace_bytes", "bs_destroy", "bs_last_error", "bs_index_free"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -147,6 +152,33 @@ def bs_destroy(ctx):
 def bs_pool_bind(ctx, n_prompts, n_rollouts, pool_tokens, rollout_offsets, prompt_rollout_begin):
     _check(ctx, lib().bs_pool_bind(ctx, n_prompts, n_rollouts, _ptr(pool_tokens), _ptr(rollout_offsets),
                                    _ptr(prompt_rollout_begin)))
+
+
+def bs_index_build(pool_tokens, rollout_offsets, prompt_rollout_begin):
+    """Host-side index build from NumPy arrays (int32, int64, int32).  Returns the blob as a NumPy int32 array (a
+    copy; the library's buffer is released)."""
+    import numpy as np
+    pt = np.ascontiguousarray(pool_tokens, dtype=np.int32)
+    ro = np.ascontiguousarray(rollout_offsets, dtype=np.int64)
+    pb = np.ascontiguousarray(prompt_rollout_begin, dtype=np.int32)
+    blob, nbytes = C.c_void_p(), C.c_size_t()
+    st = lib().bs_index_build(len(pb) - 1, pt.ctypes.data_as(C.c_void_p), ro.ctypes.data_as(C.c_void_p),
+                              pb.ctypes.data_as(C.c_void_p), C.byref(blob), C.byref(nbytes))
+    if st != BS_OK:
+        raise BsError(st, "bs_index_build failed")
+    try:
+        out = np.frombuffer(C.string_at(blob.value, nbytes.value), dtype=np.int32).copy()
+    finally:
+        lib().bs_index_free(blob)
+    return out
+
+
+def bs_index_bind(ctx, blob_host, blob_dev):
+    """blob_host: NumPy int32 array from bs_index_build (or None to unbind); blob_dev: its device copy (tensor)."""
+    if blob_host is None:
+        _check(ctx, lib().bs_index_bind(ctx, None, None, 0))
+        return
+    _check(ctx, lib().bs_index_bind(ctx, blob_host.ctypes.data_as(C.c_void_p), _ptr(blob_dev), blob_host.nbytes))
 
 
 def bs_draft_lookup(ctx, B, seq_prompt, tail_tokens, max_match, min_match, k_max, draft_tokens, draft_len):

@@ -38,6 +38,8 @@ struct bs_ctx {
   const int64_t* rollout_offsets = nullptr;
   const int32_t* prompt_rollout_begin = nullptr;
   // measurement hooks
+  const int32_t* index_blob = nullptr;   // device copy of a bs_index_build blob (optional)
+  int index_prompts = 0;
   int prof_class = 0;
   bool unfused_qkv = false;   // test hook: QKV GEMM + separate rotary kernel instead of the fused kernel
   std::vector<hipEvent_t> prof_ev;     // pairs (start, stop), created on first use
@@ -326,15 +328,32 @@ bs_status bs_pool_bind(bs_ctx* c, int n_prompts, int n_rollouts, const int32_t* 
   return BS_OK;
 }
 
+bs_status bs_index_bind(bs_ctx* c, const void* blob_host, const void* blob_dev, size_t bytes) {
+  if (!c) return BS_EINVAL;
+  if (!blob_host && !blob_dev) { c->index_blob = nullptr; c->index_prompts = 0; return BS_OK; }
+  int np = 0;
+  if (!blob_host || !blob_dev || !index_header_ok((const int32_t*)blob_host, bytes, &np))
+    return fail(c, BS_EINVAL, "bs_index_bind: not a blob of bs_index_build, or size mismatch");
+  if (((uintptr_t)blob_dev & 3) != 0) return fail(c, BS_EINVAL, "bs_index_bind: device copy must be 4-byte aligned");
+  c->index_blob = (const int32_t*)blob_dev;
+  c->index_prompts = np;
+  return BS_OK;
+}
+
 bs_status bs_draft_lookup(bs_ctx* c, int B, const int32_t* seq_prompt, const int32_t* tail_tokens, int max_match,
                           int min_match, int k_max, int32_t* draft_tokens, int32_t* draft_len, void* stream) {
   if (!c) return BS_EINVAL;
-  if (!c->pool_tokens) return fail(c, BS_ESTATE, "bs_draft_lookup: no pool bound");
+  if (!c->pool_tokens && !c->index_blob) return fail(c, BS_ESTATE, "bs_draft_lookup: no pool or index bound");
   if (!seq_prompt || !tail_tokens || !draft_tokens || !draft_len) return fail(c, BS_EINVAL, "bs_draft_lookup: null pointer");
   if (B < 1 || B > c->B_max || k_max < 0 || k_max > c->k_max || max_match < 1 || max_match > 8 || min_match < 1 ||
       min_match > max_match)
     return fail(c, BS_ESHAPE, "bs_draft_lookup: B, k_max or match lengths out of range");
   ProfScope ps(c, BS_PROF_LOOKUP, (hipStream_t)stream);
+  if (c->index_blob) {
+    launch_index_lookup(c->index_blob, c->index_prompts, seq_prompt, tail_tokens, B, max_match, min_match, k_max,
+                        draft_tokens, draft_len, (hipStream_t)stream);
+    return check_hip(c);
+  }
   launch_lookup(B, c->n_prompts, c->pool_tokens, c->rollout_offsets, c->prompt_rollout_begin, seq_prompt, tail_tokens,
                 max_match, min_match, k_max, draft_tokens, draft_len, (hipStream_t)stream);
   return check_hip(c);

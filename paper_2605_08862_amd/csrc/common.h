@@ -186,6 +186,11 @@ void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_a
                    int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
                    const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
                    hipStream_t st);
+// index.hip   prebuilt suffix-automaton index: header check (host copy of the first 8 words) and the device walk
+bool index_header_ok(const int32_t* header_host, size_t bytes, int* n_prompts);
+void launch_index_lookup(const int32_t* blob, int n_prompts, const int32_t* seq_prompt, const int32_t* tail, int B,
+                         int max_match, int min_match, int k_max, int32_t* draft_tokens, int32_t* draft_len,
+                         hipStream_t st);
 // lookup.hip
 void launch_lookup(int B, int n_prompts, const int32_t* pool_tokens, const int64_t* rollout_offsets,
                    const int32_t* prompt_rollout_begin, const int32_t* seq_prompt, const int32_t* tail,

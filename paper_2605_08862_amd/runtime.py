@@ -79,6 +79,15 @@ class Engine:
                       prompt_rollout_begin.to(self.device, torch.int32).contiguous())
         B.bs_pool_bind(self.ctx, self._pool[2].numel() - 1, self._pool[1].numel() - 1, *self._pool)
 
+    def index_bind(self, blob_host):
+        """Binds a prebuilt index (NumPy blob from binding.bs_index_build); None unbinds and returns to the scan."""
+        if blob_host is None:
+            self._index = None
+            B.bs_index_bind(self.ctx, None, None)
+            return
+        self._index = (blob_host, torch.from_numpy(blob_host).to(self.device))
+        B.bs_index_bind(self.ctx, *self._index)
+
     def draft_lookup(self, seq_prompt, tail_tokens, max_match, min_match, k_max):
         n = seq_prompt.numel()
         draft_tokens = torch.empty(n, max(k_max, 1), dtype=torch.int32, device=self.device)[:, :k_max].contiguous()

@@ -4,6 +4,7 @@ import pytest
 import torch
 
 from oracle.lookup import lookup as oracle_lookup
+from paper_2605_08862_amd import binding as Bn
 from paper_2605_08862_amd import workloads as W
 from paper_2605_08862_amd.runtime import Engine, fuse_weights
 from tests import helpers as H
@@ -19,20 +20,25 @@ def _engine(B_max, k_max):
 
 
 def _check(eng, pool, seq_prompt, tails, max_match, min_match, k_max):
+    """Both retrieval paths against the oracle: the pool scan, then the prebuilt index (bs_index_build on the
+    host, bound with bs_index_bind)."""
     toks, off, prb = pool
     eng.pool_bind(torch.tensor(toks), torch.tensor(off), torch.tensor(prb))
-    dt, dl = eng.draft_lookup(H.dev_i32(seq_prompt), H.dev_i32(tails), max_match, min_match, k_max)
-    dt, dl = dt.cpu().numpy(), dl.cpu().numpy()
-    n_hit = 0
+    refs = []
     for b in range(len(seq_prompt)):
         p = seq_prompt[b]
         rollouts = [toks[off[r]:off[r + 1]] for r in range(prb[p], prb[p + 1])]
-        ref = oracle_lookup(rollouts, tails[b], max_match, min_match, k_max)
-        assert dl[b] == len(ref), (b, dl[b], ref, dt[b])
-        assert list(dt[b][:dl[b]]) == ref, (b, dt[b], ref)
-        assert all(t == -1 for t in dt[b][dl[b]:])
-        n_hit += len(ref) > 0
-    return n_hit
+        refs.append(oracle_lookup(rollouts, tails[b], max_match, min_match, k_max))
+    for path in ("scan", "index"):
+        eng.index_bind(Bn.bs_index_build(toks, off, prb) if path == "index" else None)
+        dt, dl = eng.draft_lookup(H.dev_i32(seq_prompt), H.dev_i32(tails), max_match, min_match, k_max)
+        dt, dl = dt.cpu().numpy(), dl.cpu().numpy()
+        for b, ref in enumerate(refs):
+            assert dl[b] == len(ref), (path, b, dl[b], ref, dt[b])
+            assert list(dt[b][:dl[b]]) == ref, (path, b, dt[b], ref)
+            assert all(t == -1 for t in dt[b][dl[b]:])
+    eng.index_bind(None)
+    return sum(len(r) > 0 for r in refs)
 
 
 def test_small_vocab_dense_matches():
