@@ -110,14 +110,14 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 // Workgroup tile: BM = 32*MT rows x 4 waves x NT weight row tiles.  For SwiGLU NT == 2 and the two row
 // tiles of a wave are the gate rows and the matching up rows of the same 32 output features, so both
 // land in the same lane.  Grid: one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs,
-// each with its own L2, so the id is decoded XCD-first: with S K-splits (S in {1,2,4,8}) a split owns
-// 8/S XCDs, and inside a split each XCD takes a contiguous range of (N block, M block) tiles, M block
-// fastest.  The M blocks that share a weight tile then run back to back on one XCD and hit its L2, and
-// an XCD only ever touches its own K range of the activation matrix (measured before this mapping: the
-// down projection fetched 122 MB per launch for 38 MB of operands, every L2 pulling the whole matrix).
-// The float32 epilogues (QKV projection, residual projections) write one partial
-// [M_max, N] slab per K split, out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums
-// the slabs.  Float atomics into the residual were measured at ~25 us per launch and are not used.
+// each with its own L2, so the id is decoded XCD-first: the (K split, N block, M block) space, M block
+// fastest, is cut into 8 contiguous ranges, one per XCD.  The M blocks that share a weight tile then run back
+// to back on one XCD and hit its L2, and an XCD touches one or two K ranges of the activation matrix only
+// (measured before this mapping: the down projection fetched 122 MB per launch for 38 MB of operands, every L2
+// pulling the whole matrix).
+// The float32 epilogues (QKV projection, residual projections) write one partial [M_max, N] slab per K split,
+// out[split][m][n]; the consumer (rotary kernel, RMSNorm kernel) sums the slabs.  Float atomics into the
+// residual were measured at ~25 us per launch and are not used.
 template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
@@ -128,14 +128,13 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   using G = MfmaGemm<MT, NT, true>;
   extern __shared__ __align__(16) char lds[];
   const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
-  const int total = m_blocks * n_blocks;
-  const int xps = 8 / n_split;                             // XCDs per K split
-  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-  const int split = xcd / xps;
-  const int per_sub = (total + xps - 1) / xps;
-  if (slot >= per_sub) return;
-  const int id = (xcd % xps) * per_sub + slot;
-  if (id >= total) return;
+  // XCD-first decoding: the (split, N block, M block) space, M block fastest, is cut into 8 contiguous ranges,
+  // one per XCD (workgroup ids are dealt round-robin to the XCDs)
+  const int tiles = m_blocks * n_blocks, total = tiles * n_split;
+  const int per_xcd = (total + 7) / 8;
+  const int flat = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if ((int)(blockIdx.x / 8) >= per_xcd || flat >= total) return;
+  const int split = flat / tiles, id = flat % tiles;
   const int mb = id % m_blocks, nb = id / m_blocks;
   const int m0 = mb * G::BM;
   if (m0 >= M) return;
@@ -219,9 +218,8 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   using G = MfmaGemm<MT, NT, true>;
   constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * 32 : 4 * NT * 32;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
-  int total = m_blocks * n_blocks;
-  int xps = 8 / n_split;                                   // n_split is 1, 2, 4 or 8
-  int grid = 8 * ((total + xps - 1) / xps);
+  int total = m_blocks * n_blocks * n_split;
+  int grid = 8 * ((total + 7) / 8);
   static bool attr_set = false;              // more than 64 KiB of dynamic LDS needs an opt-in (192-row tiles)
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
@@ -278,7 +276,6 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
     if (n_split > 4 && !env_split) n_split = 4;
     if (n_split > kMaxGemmSplit) n_split = kMaxGemmSplit;
     if (n_split > nk) n_split = nk;
-    n_split = n_split >= 8 ? 8 : n_split >= 4 ? 4 : n_split >= 2 ? 2 : 1;      // a split owns 8/S whole XCDs
   }
 #define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
   if constexpr (EPI != EPI_SWIGLU) {
