@@ -387,16 +387,20 @@ __global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_ma
 // The vocabulary of each sampled row is cut into kSampleChunks chunks so that B x 32 workgroups share
 // the float64 exponentials.  Three small kernels: normaliser partials, chunk masses, pick.
 //   p_j = exp(z_j/T - max) / sum_p ;  q_j likewise ;  w_j = p_j | p_j [j != draft] | max(0, p_j - q_j)
+// Divisions by per-row constants (T, the two normalisers) are multiplications by their float64 reciprocals: a
+// float64 division costs about as much as the exponential next to it, and the one-ulp difference is far below
+// what the order of the running sums already leaves open.
 template <typename Q>
 struct SampleRow {
-  const float* z; const Q* q; double T, mxp, mxq; int tgt, mode;
-  __device__ double e_p(int j) const { return exp((double)z[j] / T - mxp); }
+  const float* z; const Q* q; double inv_T, mxp, mxq; int tgt, mode;
+  __device__ double e_p(int j) const { return exp((double)z[j] * inv_T - mxp); }
   __device__ double e_q(int j) const { return exp((double)to_f32<Q>(q[j]) - mxq); }
-  __device__ double weight(int j, double sp, double sq, int mode_now) const {
-    const double pj = e_p(j) / sp;
+  // inv_sp, inv_sq: reciprocals of the normalisers
+  __device__ double weight(int j, double inv_sp, double inv_sq, int mode_now) const {
+    const double pj = e_p(j) * inv_sp;
     if (mode_now == MODE_PLAIN) return pj;
     if (mode_now == MODE_RESID_ONEHOT) return j == tgt ? 0.0 : pj;
-    return fmax(0.0, pj - e_q(j) / sq);
+    return fmax(0.0, pj - e_q(j) * inv_sq);
   }
 };
 
@@ -407,8 +411,8 @@ __device__ __forceinline__ SampleRow<Q> sample_row(int b, int V, const float* lo
   r.mode = sb.sel_mode[b];
   r.z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
   r.q = (r.mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
-  r.T = (double)temperature;
-  r.mxp = (double)sb.sel_pmax[b] / r.T;              // max_j z_j/T: division is monotone
+  r.inv_T = 1.0 / (double)temperature;
+  r.mxp = (double)sb.sel_pmax[b] * r.inv_T;          // max_j z_j/T: the scaling is monotone
   r.mxq = (double)sb.sel_qmax[b];
   r.tgt = sb.sel_tok[b];
   return r;
@@ -444,12 +448,15 @@ __global__ void __launch_bounds__(256) sample_sum_kernel(int V, const float* __r
   }
 }
 
-__device__ __forceinline__ void sample_totals(const SamplerBufs& sb, int b, double& sp, double& sq) {
-  sp = 0.0; sq = 0.0;
+// Reciprocals of the two normalisers of sequence b (0 for an absent proposal).
+__device__ __forceinline__ void sample_totals(const SamplerBufs& sb, int b, double& inv_sp, double& inv_sq) {
+  double sp = 0.0, sq = 0.0;
   for (int c = 0; c < kSampleChunks; ++c) {          // fixed order: every workgroup gets the same totals
     sp += sb.samp_sum[((size_t)b * kSampleChunks + c) * 2];
     sq += sb.samp_sum[((size_t)b * kSampleChunks + c) * 2 + 1];
   }
+  inv_sp = 1.0 / sp;
+  inv_sq = sq > 0.0 ? 1.0 / sq : 0.0;
 }
 
 // chunk masses of the residual (index 0) and of p itself (index 1, used when the residual is empty)
@@ -467,7 +474,7 @@ __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __
   double mw = 0.0, mp = 0.0;
   for (int j = j0 + threadIdx.x; j < j1; j += 256) {
     mw += r.weight(j, sp, sq, r.mode);
-    mp += r.e_p(j) / sp;
+    mp += r.e_p(j) * sp;
   }
   mw = block_sum_f64(mw, red);
   mp = block_sum_f64(mp, red);
