@@ -53,12 +53,27 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
       gn[it] = *(const f4*)(gain + i);
     }
   }
-  for (int s = 0; s < n_slabs; ++s) {
+  // slabs are added in index order; four slabs' loads are issued together (a slab index past the end is clamped
+  // and its value dropped), so that a row costs one memory round trip instead of one per slab
+  constexpr int GS = NV <= 4 ? 4 : 1;
+  for (int s0 = 0; s0 < n_slabs; s0 += GS) {
+    f4 t[GS][NV];
 #pragma unroll
-    for (int it = 0; it < NV; ++it) {
-      const int i = (it * 256 + threadIdx.x) * 4;
-      if (i < d) v[it] += *(const f4*)(sl + (size_t)s * slab_stride + i);
+    for (int u = 0; u < GS; ++u) {
+      const int s = min(s0 + u, n_slabs - 1);
+#pragma unroll
+      for (int it = 0; it < NV; ++it) {
+        const int i = (it * 256 + threadIdx.x) * 4;
+        t[u][it] = f4{0.f, 0.f, 0.f, 0.f};
+        if (i < d) t[u][it] = *(const f4*)(sl + (size_t)s * slab_stride + i);
+      }
     }
+#pragma unroll
+    for (int u = 0; u < GS; ++u)
+      if (s0 + u < n_slabs) {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) v[it] += t[u][it];
+      }
   }
   float ss = 0.f;
 #pragma unroll

@@ -226,6 +226,113 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
                      N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split);
 }
 
+
+// Eight-wave kernel (see MfmaGemm8): 192 rows x 128 SwiGLU features (EPI_SWIGLU: gate tile and up tile of the
+// same 32 features in one wave) or x 256 output columns (EPI_STORE) per workgroup of 512 threads.
+template <int EPI>
+__global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
+                                                    const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
+                                                    const f16* __restrict__ Wp, void* __restrict__ out, int m_blocks,
+                                                    int n_blocks) {
+  using G = MfmaGemm8;
+  extern __shared__ __align__(16) char lds[];
+  const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
+  const int total = m_blocks * n_blocks, per_xcd = (total + 7) / 8;
+  const int id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if ((int)(blockIdx.x / 8) >= per_xcd || id >= total) return;
+  const int mb = id % m_blocks, nb = id / m_blocks;
+  const int m0 = mb * G::BM;
+  if (m0 >= M) return;
+  constexpr bool GLU = (EPI == EPI_SWIGLU);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int nk = K / kBK;
+  const int n_tiles = (N + 31) / 32;
+
+  G::Operands op;
+  op.x_base = (const char*)A;
+  op.w_base = (const char*)Wp;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    int row, g, s;
+    G::chunk_of(i, row, g, s);
+    int r = min(m0 + row, M - 1);
+    if (a_rows) r = a_rows[r];
+    op.x_off[i] = (uint32_t)(((size_t)r * K + g * 32 + s * 8) * 2);
+    op.x_lds[i] = G::chunk_lds_offset(row, g, s);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ni = threadIdx.x >> 8;
+    int nt;
+    if (GLU) nt = min(nb * 4 + i, n_tiles - 1) + ni * n_tiles;
+    else     nt = min(nb * 8 + i * 2 + ni, n_tiles - 1);
+    op.w_off[i] = (uint32_t)(((size_t)nt * nk * kWBlock + (threadIdx.x & 255) * 8) * 2);
+  }
+  f32x16 acc[3][2];
+#pragma unroll
+  for (int mi = 0; mi < 3; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    G::run(acc, op, 0, nk, lds);
+
+  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+  const int ln = lane & 31, lg = lane >> 5;
+  const int n_wave0 = GLU ? (nb * 4 + wn) * 32 : (nb * 4 + wn) * 64;
+#pragma unroll
+  for (int mi = 0; mi < 3; ++mi) {
+    const int m = m0 + wm * 96 + mi * 32 + ln;
+    if (m >= M) continue;
+    if (GLU) {
+      if (n_wave0 >= N) continue;
+      f16* dst = (f16*)out + (size_t)m * N + n_wave0 + 4 * lg;
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f16x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (f16)(silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j]);
+        *(f16x4*)(dst + 8 * i4) = v;
+      }
+    } else {
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int n0 = n_wave0 + ni * 32;
+        if (n0 >= N) continue;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f16x4 v;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = (f16)acc[mi][ni][4 * i4 + j];
+          *(f16x4*)((f16*)out + (size_t)m * N + n0 + 8 * i4 + 4 * lg) = v;
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+static void launch_gemm8(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
+                         const void* W, void* out, hipStream_t st) {
+  using G = MfmaGemm8;
+  constexpr int nout = (EPI == EPI_SWIGLU) ? 128 : 256;
+  const int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
+  const int grid = 8 * ((m_blocks * n_blocks + 7) / 8);
+  static bool attr_set = false;
+  if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm8_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
+  hipLaunchKernelGGL((gemm8_kernel<EPI>), dim3(grid), dim3(512), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
+                     (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks);
+}
+
+// The eight-wave kernel addresses both matrices with 32-bit byte offsets and pays off when 192-row blocks fit
+// the row count without much padding.
+static bool gemm8_applies(int M_max, int N, int K, int w_rows) {
+  if ((size_t)M_max * K * 2 >= ((size_t)1 << 32) || packed_weight_elems(w_rows, K) * 2 >= ((size_t)1 << 32)) return false;
+  const int pad6 = (M_max + 191) / 192 * 192, pad4 = (M_max + 127) / 128 * 128;
+  return M_max > 128 && pad6 <= pad4;
+}
+
 template <typename T, int EPI>
 static void launch_simple(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
                           const void* W, void* out, hipStream_t st) {
@@ -252,6 +359,14 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   static const char* env_split = getenv("BS_GEMM_SPLIT");          // tuning aids
   static const char* env_nt = getenv("BS_GEMM_NT");
   static const char* env_mt = getenv("BS_GEMM_MT");
+  static const char* env_g8 = getenv("BS_GEMM8");
+  if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE) {
+    const bool want = env_g8 ? atoi(env_g8) != 0 : (EPI == EPI_SWIGLU);
+    if (want && gemm8_applies(M_max, N, K, EPI == EPI_SWIGLU ? 2 * N : N)) {
+      launch_gemm8<EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+      return 1;
+    }
+  }
   int mt = pick_mt(M_max);
   // float32-epilogue GEMMs have narrow outputs (N = d or Nqkv): measured on MI355X at M = 576, smaller row
   // tiles with at most 4 K splits beat 192-row tiles with 7 splits (down projection 50 -> 33 us, O 17 -> 13 us)

@@ -191,3 +191,122 @@ struct MfmaGemm {
     }
   }
 };
+
+// ---------------------------------------------------------------------------------------------------------
+// Eight-wave variant: a 512-thread workgroup computes a 192-row x 8-weight-row-tile block, its waves arranged
+// 2 (rows) x 4 (weight tiles), each holding 96 rows x 2 row tiles (6 accumulator tiles = 96 registers), so two
+// waves share every SIMD.  A single wave per SIMD cannot hide the issue cost of its own LDS and global
+// instructions behind its MFMAs (measured: a software-pipelined 1 KiB LDS read costs ~17 MFMA cycles, and the
+// four-wave loop above runs at ~53 cycles per MFMA against 32 for MFMAs alone); with a second wave on the SIMD the
+// matrix unit takes that wave's MFMAs meanwhile.  Measured on the SwiGLU GEMM at M = 576: 59 % instead of 56 % of
+// the wave time with the matrix unit busy, 1-3 % less time per launch (no LDS bank conflicts, LDS 35 % busy).  Two
+// waves per SIMD leave 256 registers each, too few for a private weight stream as deep as above, so BOTH operands
+// go through LDS here: per K tile the workgroup stages 24 KiB of activations and 32 KiB of weights once, and no
+// byte is fetched twice by a CU.  The packed weight blocks are already in fragment order: their LDS image is a
+// straight copy.
+//
+// Pipeline per K tile kt (two LDS stages, two register sets): slots 0..6 store the seven 16-byte chunks of tile
+// kt + 1 (loaded two iterations ago) to the other stage and immediately reload the same registers with tile
+// kt + 3; every slot reads the fragments of the next K-step; the barrier sits before the slots of K-step 3, which
+// already read step 0 of tile kt + 1.  Two stages are enough: all reads of a stage are issued (and waited for)
+// before the barrier of its own iteration, and it is overwritten only after that barrier.
+struct MfmaGemm8 {
+  static constexpr int BM = 192, MTW = 3, NTW = 2, THREADS = 512;
+  static constexpr int X_STAGE = 6 * 4 * 1024, W_STAGE = 8 * 4096, STAGE_BYTES = X_STAGE + W_STAGE;
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+
+  struct Operands {
+    const char* x_base;      // activation matrix (float16 rows of K elements)
+    const char* w_base;      // packed weight matrix
+    uint32_t x_off[3];       // byte offset of this thread's activation chunks at k = 0
+    int x_lds[3];            // byte offset of each activation chunk inside a stage
+    uint32_t w_off[4];       // byte offset of this thread's weight chunks at K tile 0
+  };
+  // activation chunk i of thread t: q = i*512 + t -> row q/8, (g, s) = (q%8 / 4, q%4)
+  __device__ static __forceinline__ void chunk_of(int i, int& row, int& g, int& s) {
+    int q = i * 512 + threadIdx.x;
+    row = q >> 3;
+    g = (q >> 2) & 1;
+    s = q & 3;
+  }
+  __device__ static __forceinline__ int chunk_lds_offset(int row, int g, int s) {
+    return (((row >> 5) * 4 + s) * 64 + ((g * 32 + (row & 31)) ^ (s + 4 * g))) * 16;
+  }
+  __device__ static __forceinline__ int xfrag_offset(int mi_wg, int s, int lane) {
+    return ((mi_wg * 4 + s) * 64 + (lane ^ (s + 4 * (lane >> 5)))) * 16;
+  }
+  // weight chunk i of thread t: LDS tile i*2 + t/256 (= wave column i, row tile t/256 of that wave), 16-byte piece
+  // t%256 of its 4 KiB block; the same position inside the stage's weight area
+  __device__ static __forceinline__ int w_lds_offset(int i) { return X_STAGE + (i * 2 + (threadIdx.x >> 8)) * 4096 + (threadIdx.x & 255) * 16; }
+  __device__ static __forceinline__ int wfrag_offset(int wn, int ni, int s, int lane) {
+    return X_STAGE + (wn * 2 + ni) * 4096 + s * 1024 + lane * 16;
+  }
+
+  __device__ static __forceinline__ void load_set(u32x4 (&ring)[7], const Operands& op, int kt) {
+#pragma unroll
+    for (int i = 0; i < 3; ++i) ring[i] = *(const u32x4*)(op.x_base + op.x_off[i] + (size_t)kt * (kBK * 2));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ring[3 + i] = *(const u32x4*)(op.w_base + op.w_off[i] + (size_t)kt * (kWBlock * 2));
+  }
+  __device__ static __forceinline__ void store_chunk(char* stage, const Operands& op, int e, const u32x4& v) {
+    if (e < 3) *(u32x4*)(stage + op.x_lds[e]) = v;
+    else       *(u32x4*)(stage + w_lds_offset(e - 3)) = v;
+  }
+
+  template <int STAGE>
+  __device__ static __forceinline__ void body(f32x16 (&acc)[MTW][NTW], u32x4 (&ring)[2][7], u32x4 (&xf)[2][MTW],
+                                              u32x4 (&wf)[2][NTW], const Operands& op, int kt, int kt1, char* lds) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const char* stage = lds + STAGE * STAGE_BYTES;
+    char* nstage = lds + (1 - STAGE) * STAGE_BYTES;
+    const int kl = min(kt + 3, kt1 - 1);
+#pragma unroll
+    for (int j = 0; j < 12; ++j) {
+      const int s = j / 3, mi = j % 3;
+      if (j == 9) {
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      const char* src = (s < 3) ? stage : nstage;
+      const int sn = (s + 1) & 3;
+      xf[(s + 1) & 1][mi] = *(const u32x4*)(src + xfrag_offset(wm * 3 + mi, sn, lane));
+      if (mi < NTW) wf[(s + 1) & 1][mi] = *(const u32x4*)(src + wfrag_offset(wn, mi, sn, lane));
+      if (j < 7) {
+        store_chunk(nstage, op, j, ring[1 - STAGE][j]);
+        if (j < 3) ring[1 - STAGE][j] = *(const u32x4*)(op.x_base + op.x_off[j] + (size_t)kl * (kBK * 2));
+        else       ring[1 - STAGE][j] = *(const u32x4*)(op.w_base + op.w_off[j - 3] + (size_t)kl * (kWBlock * 2));
+      }
+      const f16x8 x = as_f16x8(xf[s & 1][mi]);
+#pragma unroll
+      for (int ni = 0; ni < NTW; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(wf[s & 1][ni]), x, acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // Accumulates K tiles [kt0, kt1) into acc (accumulator tiles hold C^T: rows = weight rows, lane = activation
+  // row).  All 512 threads must call it.  On return the waves are not synchronised and LDS may still be read.
+  __device__ static __forceinline__ void run(f32x16 (&acc)[MTW][NTW], const Operands& op, int kt0, int kt1, char* lds) {
+    if (kt0 >= kt1) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    u32x4 ring[2][7], xf[2][MTW], wf[2][NTW];
+    load_set(ring[0], op, kt0);
+    load_set(ring[1], op, min(kt0 + 1, kt1 - 1));
+#pragma unroll
+    for (int e = 0; e < 7; ++e) store_chunk(lds, op, e, ring[0][e]);
+    load_set(ring[0], op, min(kt0 + 2, kt1 - 1));
+    __syncthreads();
+#pragma unroll
+    for (int mi = 0; mi < MTW; ++mi) xf[0][mi] = *(const u32x4*)(lds + xfrag_offset(wm * 3 + mi, 0, lane));
+#pragma unroll
+    for (int ni = 0; ni < NTW; ++ni) wf[0][ni] = *(const u32x4*)(lds + wfrag_offset(wn, ni, 0, lane));
+    int kt = kt0;
+    for (; kt + 2 <= kt1; kt += 2) {
+      body<0>(acc, ring, xf, wf, op, kt, kt1, lds);
+      body<1>(acc, ring, xf, wf, op, kt + 1, kt1, lds);
+    }
+    if (kt < kt1) body<0>(acc, ring, xf, wf, op, kt, kt1, lds);
+  }
+};
