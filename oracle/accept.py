@@ -26,10 +26,20 @@ documented convention, not a hidden constant):
     token in the acceptance length); emit_bonus=False is Alg. 1 literally.
   * an accepted EOS ends the block (Alg. 1); nothing is emitted after it.
   * an empty draft block is plain sampling from row 0 (Alg. 1, first branch).
+  * top-k / top-p (Sec. 3.2 defines p_t as the distribution "after temperature
+    scaling and any top-p/top-k filtering" and says no more): tokens are ranked
+    by logit, equal logits by lower index first; top-k keeps the first k of the
+    ranking; top-p then keeps the shortest prefix of what is left whose mass
+    reaches top_p times the mass of what is left (a token stays while the mass
+    ranked before it is below that); the kept probabilities are renormalised.
+    top_k <= 0 or >= V and top_p >= 1 switch the respective filter off.
 
 Pin status: pinned (chi-square against the target distribution, closed-form
 acceptance probabilities, greedy-path full acceptance, k = 0 == plain decode,
-one-hot q == q_logits=None).
+one-hot q == q_logits=None; filtering: top_k = 1 == temperature 0, filters off
+== unfiltered, closed-form nucleus of a geometric distribution, the three
+defining properties of the kept set checked by an independent brute force,
+chi-square of the emitted token against the filtered target).
 """
 import numpy as np
 
@@ -43,6 +53,41 @@ def target_probs(z, temperature):
     x = z / temperature
     e = np.exp(x - np.max(x))
     return e / np.sum(e)
+
+
+def kept_tokens(z, temperature, top_k=0, top_p=1.0):
+    """Tokens that survive top-k then top-p, in ranking order, and the boundary margin.
+
+    margin = distance of top_p * S from the nearer of the two cumulative masses
+    that decide the last kept token, divided by S (inf when top-p is off): a
+    tiny margin marks a decision that rounding could turn."""
+    z = np.asarray(z, dtype=np.float64)
+    V = z.shape[0]
+    p = target_probs(z, temperature)
+    order = np.lexsort((np.arange(V), -z))               # by logit descending, then index ascending
+    if 0 < top_k < V:
+        order = order[:top_k]
+    margin = np.inf
+    if top_p < 1.0:
+        C = np.cumsum(p[order])
+        t = float(top_p) * C[-1]
+        n = int(np.searchsorted(C, t, side="left"))      # first n with C_n >= t
+        n = min(n, len(order) - 1)
+        below = C[n - 1] if n > 0 else 0.0
+        margin = min(abs(C[n] - t), abs(t - below)) / C[-1]
+        order = order[:n + 1]
+    return order, margin
+
+
+def filtered_probs(z, temperature, top_k=0, top_p=1.0):
+    """p_t of Sec. 3.2: softmax(z / T), filtered and renormalised."""
+    p = target_probs(z, temperature)
+    if temperature == 0.0 or (not 0 < top_k < p.shape[0] and top_p >= 1.0):
+        return p
+    keep, _ = kept_tokens(z, temperature, top_k, top_p)
+    out = np.zeros_like(p)
+    out[keep] = p[keep] / np.sum(p[keep])
+    return out
 
 
 def proposal_probs(ql):
@@ -80,7 +125,7 @@ class VerifyResult:
 
 
 def verify_sequence(logits, drafts, u_accept, u_sample, q_logits=None,
-                    temperature=1.0, eos_id=-1, emit_bonus=True):
+                    temperature=1.0, eos_id=-1, emit_bonus=True, top_k=0, top_p=1.0):
     """Alg. 1's verify loop for ONE sequence and ONE draft block.
 
     logits   [k+1, V]  row i = target logits after [last, x~_1..x~_i]
@@ -94,7 +139,7 @@ def verify_sequence(logits, drafts, u_accept, u_sample, q_logits=None,
     assert logits.shape[0] == k + 1
     res = VerifyResult()
     for t in range(k):
-        p = target_probs(logits[t], temperature)
+        p = filtered_probs(logits[t], temperature, top_k, top_p)
         a = int(drafts[t])
         if q_logits is None:
             q = np.zeros_like(p)
@@ -118,7 +163,7 @@ def verify_sequence(logits, drafts, u_accept, u_sample, q_logits=None,
         res.tokens.append(x)
         return res
     if emit_bonus or k == 0:
-        p = target_probs(logits[k], temperature)
+        p = filtered_probs(logits[k], temperature, top_k, top_p)
         x, res.sample_margin = inverse_cdf(p, u_sample)
         res.sampled_row = k
         res.tokens.append(x)
@@ -126,7 +171,7 @@ def verify_sequence(logits, drafts, u_accept, u_sample, q_logits=None,
 
 
 def verify_batch(logits_rows, draft_tokens, draft_len, u_accept, u_sample,
-                 q_logits_rows=None, temperature=1.0, eos_id=-1, emit_bonus=True):
+                 q_logits_rows=None, temperature=1.0, eos_id=-1, emit_bonus=True, top_k=0, top_p=1.0):
     """Batch wrapper over packed rows.
 
     logits_rows   [M, V]   sequence b owns rows row0_b .. row0_b + k_b,
@@ -143,15 +188,15 @@ def verify_batch(logits_rows, draft_tokens, draft_len, u_accept, u_sample,
         ql = None if q_logits_rows is None else q_logits_rows[d0:d0 + k]
         out.append(verify_sequence(logits_rows[r0:r0 + k + 1], draft_tokens[b][:k],
                                    u_accept[b], u_sample[b], ql,
-                                   temperature, eos_id, emit_bonus))
+                                   temperature, eos_id, emit_bonus, top_k, top_p))
         r0 += k + 1
         d0 += k
     return out
 
 
-def plain_sample(logits_row, u_sample, temperature=1.0):
+def plain_sample(logits_row, u_sample, temperature=1.0, top_k=0, top_p=1.0):
     """Ordinary auto-regressive sampling of one token (no speculation)."""
-    return inverse_cdf(target_probs(logits_row, temperature), u_sample)[0]
+    return inverse_cdf(filtered_probs(logits_row, temperature, top_k, top_p), u_sample)[0]
 
 
 def rollout(next_logits, retrieve, prefix, max_len, uniforms, temperature=1.0,
