@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scan-lookup", action="store_true",
                     help="draft lookup by scanning the raw pool instead of walking the prebuilt suffix index")
+    ap.add_argument("--top-k", type=int, default=0, help="top-k filter of the target distribution (0: off, the headline)")
+    ap.add_argument("--top-p", type=float, default=1.0, help="top-p filter of the target distribution (1.0: off, the headline)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic) for calibrating rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -153,6 +155,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     wl = build_workload(args)
+    filtered = args.top_k > 0 or args.top_p < 1.0
+    if filtered:
+        wl["eng"].set_filter(args.top_k, args.top_p)
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
@@ -183,7 +188,8 @@ def main():
         "config": {"workload": "s1p5b_b%d_c%d_k%d (%s1.5B-shape bf16 decoder, %d layers, dense q, agreement 0.7)"
                                % (args.batch, args.context, args.k,
                                   "BASELINE configs[1]: " if (args.batch, args.context, args.k, args.layers) == (64, 2048, 8, 28)
-                                  else "NOT the headline configuration: ", args.layers),
+                                  and not filtered else "NOT the headline configuration: ", args.layers)
+                               + (" top_k=%d top_p=%g" % (args.top_k, args.top_p) if filtered else ""),
                    "batch": args.batch, "context": args.context, "k": args.k},
         "accepted_draft_tokens_per_s": accepted / dt,
         "emitted_per_seq_per_step": emitted / (args.steps * args.batch),
@@ -193,7 +199,7 @@ def main():
                          "pool_tokens": wl["pool_tokens"], "index_build_s_host": wl["index_build_s"]},
     }
     res.update(measure_roofline(wl, args))
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not filtered:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))
 

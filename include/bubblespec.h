@@ -196,6 +196,21 @@ bs_status bs_accept_resample_logits(bs_ctx* ctx, int B, int vocab, const float* 
                                     int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted,
                                     uint32_t* near_tie, void* stream);
 
+/* Sec. 3.2 defines p_t as the decoding distribution "after temperature scaling and any top-p / top-k
+ * filtering": selects that filtering for all following bs_accept_resample / bs_accept_resample_logits
+ * calls of the context.  Tokens are ranked by logit (equal logits: lower index first); top_k keeps the
+ * first top_k of the ranking (top_k <= 0 or >= vocab: off); top_p then keeps the shortest prefix of
+ * what is left whose mass reaches top_p times the mass of what is left (top_p >= 1: off); the kept
+ * probabilities are renormalised and take the place of p_i in the accept test, the residual and the
+ * bonus / plain sample.  Temperature 0 is unaffected (the arg-max is always kept).
+ * logits_scratch (dev, float32, at least B_max*(k_max+1)*vocab elements of the context's limits, owned
+ * by the caller, must stay valid while the filter is on): bf16 models write every row's logits there,
+ * because finding a row's threshold needs the row in memory (the unfiltered path keeps only per-tile
+ * statistics); may be NULL for float32 models and for bs_accept_resample_logits.  Host call, no GPU
+ * work.  Errors: BS_EINVAL (null ctx, top_p <= 0 or NaN); a filtered accept call fails with BS_ESTATE
+ * if a bf16 model has no scratch and with BS_ESHAPE if vocab > 262136. */
+bs_status bs_set_filter(bs_ctx* ctx, int top_k, float top_p, float* logits_scratch);
+
 /* Alg. 1 "y <- y o a": keeps n_commit[b] of the k_b+1 tentative rows of the last verify step:
  * ctx_len[seq_slot[b]] += n_commit[b].  Normal use: n_commit = n_accepted + 1 (the last token and
  * the accepted drafts; the sampled token becomes the next step's last_token).  Prefill: verify a

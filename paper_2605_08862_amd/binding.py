@@ -19,7 +19,7 @@ STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", 
 EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs_pool_bind", "bs_draft_lookup",
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
            "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end", "bs_index_build", "bs_index_free",
-           "bs_index_bind"]
+           "bs_index_bind", "bs_set_filter"]
 PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
                 "sample": 7, "lookup": 8, "empty": 9}
 
@@ -73,6 +73,7 @@ def lib():
         L.bs_accept_resample.argtypes = [vp, i32, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.bs_accept_resample_logits.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp,
                                                 vp, vp, vp, vp]
+        L.bs_set_filter.argtypes = [vp, i32, f32, vp]
         L.bs_kv_commit.argtypes = [vp, i32, vp, vp, vp]
         L.bs_kv_write.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.bs_kv_read.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
@@ -207,6 +208,10 @@ def bs_accept_resample_logits(ctx, B, vocab, logits, draft_tokens, draft_len, k_
                                                 _ptr(n_emitted), _ptr(near_tie), _stream()))
 
 
+def bs_set_filter(ctx, top_k, top_p, logits_scratch):
+    _check(ctx, lib().bs_set_filter(ctx, int(top_k), float(top_p), _ptr(logits_scratch)))
+
+
 def bs_kv_commit(ctx, B, seq_slot, n_commit):
     _check(ctx, lib().bs_kv_commit(ctx, B, _ptr(seq_slot), _ptr(n_commit), _stream()))
 
@@ -249,3 +254,17 @@ def bs_debug_unfused_qkv(ctx, on):
     f.argtypes = [C.c_void_p, C.c_int]
     f.restype = None
     f(ctx, 1 if on else 0)
+
+
+def bs_debug_filter_rows(ctx, n_rows):
+    """Test hook (not part of the public ABI): per-row threshold of the last filtered accept step:
+    (ranking key uint32 as int64, index cut int32, log of the kept mass float32), each [n_rows]."""
+    f = lib().bs_debug_copy
+    f.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    f.restype = C.c_int
+    key = torch.empty(n_rows, dtype=torch.int32, device="cuda")
+    idx = torch.empty(n_rows, dtype=torch.int32, device="cuda")
+    lse = torch.empty(n_rows, dtype=torch.float32, device="cuda")
+    for which, t in ((7, key), (8, idx), (9, lse)):
+        _check(ctx, f(ctx, which, t.data_ptr(), t.numel() * 4, _stream()))
+    return key.to(torch.int64) & 0xffffffff, idx, lse

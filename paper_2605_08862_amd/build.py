@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbubblespec.so")
-SOURCES = ["api.hip", "plan.hip", "elementwise.hip", "gemm.hip", "qkv_rope.hip", "attention.hip", "sampler.hip", "lookup.hip", "index.hip"]
+SOURCES = ["api.hip", "plan.hip", "elementwise.hip", "gemm.hip", "qkv_rope.hip", "attention.hip", "sampler.hip", "lookup.hip", "index.hip", "filter.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-munsafe-fp-atomics",      # float32 atomic add as the hardware instruction, not a CAS loop
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

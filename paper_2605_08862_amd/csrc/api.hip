@@ -41,6 +41,9 @@ struct bs_ctx {
   const int32_t* index_blob = nullptr;   // device copy of a bs_index_build blob (optional)
   int index_prompts = 0;
   int prof_class = 0;
+  int top_k = 0;              // top-k / top-p filter of the target distribution (bs_set_filter); 0 / 1.0 = off
+  float top_p = 1.0f;
+  float* filter_logits = nullptr;   // bf16 models: caller's [M_max, V] float32 scratch for the filtered path
   bool unfused_qkv = false;   // test hook: QKV GEMM + separate rotary kernel instead of the fused kernel
   std::vector<hipEvent_t> prof_ev;     // pairs (start, stop), created on first use
   size_t prof_used = 0;
@@ -140,6 +143,9 @@ size_t carve(bs_ctx* c, char* base) {
   sb.sel_mode = w.take<int32_t>(B);
   sb.sel_qrow = w.take<int32_t>(B);
   sb.sel_tok = w.take<int32_t>(B);
+  sb.f_key = w.take<uint32_t>(M);
+  sb.f_idx = w.take<int32_t>(M);
+  sb.f_lse = w.take<float>(M);
   if (s.dtype == BS_F32) {
     c->full_logits = w.take<float>((size_t)M * s.V);
     sb.sel_logits = nullptr;
@@ -429,6 +435,12 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
   const float* sample_base;
   bool rows_selected = false;
   int n_vtiles;
+  // top-k / top-p act on a sampled distribution only; they need every row's float32 logits in memory
+  FilterArgs filter{0, c->top_k, c->top_p, nullptr, V};
+  filter.on = (temperature > 0.f && ((c->top_k > 0 && c->top_k < V) || c->top_p < 1.0f)) ? 1 : 0;
+  if (filter.on && V > kFilterMaxVocab) return fail(c, BS_ESHAPE, "accept_resample: top-k / top-p support at most 262136 vocabulary entries");
+  if (filter.on && !given_logits && s.dtype == BS_BF16 && !c->filter_logits)
+    return fail(c, BS_ESTATE, "accept_resample: top-k / top-p on a bf16 model need the logits scratch of bs_set_filter");
   if (given_logits) {
     launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, 0, 0, 0, st);
     launch_logit_stats(p, M_max, V, given_logits, inv_temp, c->sb, st);
@@ -441,19 +453,24 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
     sample_base = c->full_logits;
   } else {
     { ProfScope ps(c, BS_PROF_LMHEAD, st);
-      launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, inv_temp, c->sb, nullptr, st); }
+      launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, inv_temp, c->sb, filter.on ? c->filter_logits : nullptr, st); }
     n_vtiles = (V + 63) / 64;
-    sample_base = c->sb.sel_logits;
-    rows_selected = true;
+    if (filter.on) {
+      sample_base = c->filter_logits;                  // every row is in memory: no second LM-head pass
+    } else {
+      sample_base = c->sb.sel_logits;
+      rows_selected = true;
+    }
   }
+  filter.logits = sample_base;
   if (q_logits) launch_q_stats(p, M_max, V, q_logits, q_dtype, c->sb, st);
   launch_accept_scan(p, B, k_max, M_max, n_vtiles, q_logits != nullptr, temperature, eos_id, emit_bonus, u_accept, c->sb,
-                     n_accepted, out_tokens, n_emitted, near_tie, st);
+                     filter, n_accepted, out_tokens, n_emitted, near_tie, st);
   if (temperature > 0.f) {
     if (rows_selected) launch_lmhead_rows(s, B, c->hf, c->lm_head, c->sb, st);
     ProfScope ps(c, BS_PROF_SAMPLE, st);
-    launch_sample(B, k_max, V, sample_base, rows_selected, q_logits, q_dtype, temperature, u_sample, c->sb, n_accepted,
-                  out_tokens, n_emitted, near_tie, st);
+    launch_sample(B, k_max, V, sample_base, rows_selected, q_logits, q_dtype, temperature, filter.on != 0, u_sample, c->sb,
+                  n_accepted, out_tokens, n_emitted, near_tie, st);
   }
   return check_hip(c);
 }
@@ -503,6 +520,15 @@ bs_status bs_accept_resample_logits(bs_ctx* c, int B, int vocab, const float* lo
                        emit_bonus, u_accept, u_sample, n_accepted, out_tokens, n_emitted, near_tie, (hipStream_t)stream);
 }
 
+bs_status bs_set_filter(bs_ctx* c, int top_k, float top_p, float* logits_scratch) {
+  if (!c) return BS_EINVAL;
+  if (!(top_p > 0.f)) return fail(c, BS_EINVAL, "bs_set_filter: top_p must be in (0, 1] (>= 1 switches it off)");
+  c->top_k = top_k > 0 ? top_k : 0;
+  c->top_p = top_p < 1.0f ? top_p : 1.0f;
+  c->filter_logits = logits_scratch;
+  return BS_OK;
+}
+
 bs_status bs_kv_commit(bs_ctx* c, int B, const int32_t* seq_slot, const int32_t* n_commit, void* stream) {
   if (!c) return BS_EINVAL;
   if (!seq_slot || !n_commit) return fail(c, BS_EINVAL, "bs_kv_commit: null pointer");
@@ -550,7 +576,8 @@ bs_status bs_poll_status(bs_ctx* c, void* stream, int32_t* fault_out) {
 void bs_debug_unfused_qkv(bs_ctx* c, int on) { if (c) c->unfused_qkv = on != 0; }
 
 // Not part of the public ABI: address of an intermediate buffer of the last verify step, for
-// kernel-level debugging (0 h, 1 normed rows, 2 qkv f32, 3 q, 4 attention out, 5 mlp act, 6 final rows).
+// kernel-level debugging (0 h, 1 normed rows, 2 qkv f32, 3 q, 4 attention out, 5 mlp act, 6 final rows), or of
+// the last accept step (7, 8, 9: per-row filter threshold key, index cut, log of the kept mass).
 void* bs_debug_buffer(bs_ctx* c, int which) {
   if (!c) return nullptr;
   switch (which) {
@@ -561,8 +588,18 @@ void* bs_debug_buffer(bs_ctx* c, int which) {
     case 4: return c->attn_out;
     case 5: return c->act;
     case 6: return c->hf;
+    case 7: return c->sb.f_key;
+    case 8: return c->sb.f_idx;
+    case 9: return c->sb.f_lse;
     default: return nullptr;
   }
+}
+
+// Not part of the public ABI: copies the first `bytes` bytes of a bs_debug_buffer to a device buffer of the caller.
+int bs_debug_copy(bs_ctx* c, int which, void* dst, size_t bytes, void* stream) {
+  void* src = bs_debug_buffer(c, which);
+  if (!src || !dst) return BS_EINVAL;
+  return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream) == hipSuccess ? BS_OK : BS_EHIP;
 }
 
 }  // extern "C"

@@ -169,7 +169,20 @@ struct SamplerBufs {
   float* sel_pmax; float* sel_qmax;                      // [B_max] raw maxima of the sampled row / its q row
   double* samp_sum; double* samp_mass;                   // [B_max, 32 chunks, 2] sampling partials
   float* sel_logits;                                     // [B_max, V]
+  uint32_t* f_key; int32_t* f_idx; float* f_lse;         // [M_max] top-k / top-p threshold of each row (filter.hip)
 };
+
+// Ranking key of a logit for the top-k / top-p filter: unsigned order == numeric order (-0 counts as +0), so
+// "token j of row r is kept" reads  key > f_key[r] || (key == f_key[r] && j <= f_idx[r]).
+__device__ __forceinline__ uint32_t filter_key(float z) {
+  if (z == 0.0f) z = 0.0f;
+  const uint32_t u = __float_as_uint(z);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ bool filter_keeps(uint32_t key, int j, uint32_t f_key, int f_idx) {
+  return key > f_key || (key == f_key && j <= f_idx);
+}
+struct FilterArgs { int on; int top_k; float top_p; const float* logits; int V; };
 int lmhead_vtiles(int V);
 void launch_lmhead_stats(const Shape& s, const Plan& p, int M_max, const void* hf, const void* lm_head,
                          float inv_temp, const SamplerBufs& sb, float* logits_debug, hipStream_t st);
@@ -180,11 +193,15 @@ void launch_lmhead_rows(const Shape& s, int B, const void* hf, const void* lm_he
 void launch_q_stats(const Plan& p, int M_max, int V, const void* q_logits, int q_dtype, const SamplerBufs& sb,
                     hipStream_t st);
 void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles, bool dense_q, float temperature,
-                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
-                        int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st);
+                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, const FilterArgs& filter,
+                        int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st);
 void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
-                   int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
+                   int q_dtype, float temperature, bool filter_on, const float* u_sample, const SamplerBufs& sb,
                    const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
+                   hipStream_t st);
+// filter.hip   per-row threshold of the top-k / top-p filter (needs row_max of the same logits)
+constexpr int kFilterMaxVocab = 262136;
+void launch_filter(const Plan& p, int M_max, float temperature, const FilterArgs& filter, const SamplerBufs& sb,
                    hipStream_t st);
 // index.hip   prebuilt suffix-automaton index: header check (host copy of the first 8 words) and the device walk
 bool index_header_ok(const int32_t* header_host, size_t bytes, int* n_prompts);

@@ -73,6 +73,7 @@ __global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const
   if (n_wave0 >= V) return;
 
   // accumulator (SWAP): rows = vocabulary entries n_wave0 + ni*32 + acc_row, lane column = token
+  const bool store_vec = (V & 3) == 0 && ((uintptr_t)store & 15) == 0;   // V % 4 == 0: groups of four never straddle V
 #pragma unroll
   for (int mi = 0; mi < kLmMT; ++mi) {
     const int m = m0 + mi * 32 + acc_col(lane);
@@ -90,9 +91,21 @@ __global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const
           if (n < V) {
             if (z > mx) { mx = z; arg = n; }
             if (valid && n == tgt) sb.z_target[m] = z;
-            if (valid && store) store[(size_t)m * V + n] = z;
+            if (valid && store && !store_vec) store[(size_t)m * V + n] = z;
           }
         }
+      if (valid && store && store_vec) {
+        // registers 4 i4 .. 4 i4 + 3 of a lane are four consecutive vocabulary entries: 16-byte stores
+#pragma unroll
+        for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const int n = n_wave0 + ni * 32 + acc_row(lane, 4 * i4);
+            if (n + 3 < V)
+              *(f32x4*)(store + (size_t)m * V + n) =
+                  f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
+          }
+      }
       const float mx_o = __shfl_xor(mx, 32);
       const int arg_o = __shfl_xor(arg, 32);
       if (mx_o > mx || (mx_o == mx && arg_o < arg)) { mx = mx_o; arg = arg_o; }
@@ -322,7 +335,8 @@ __global__ void __launch_bounds__(256) q_stats_kernel(Plan p, int V, const Q* __
 // ------------------------------------------------------------------ accept scan (Alg. 1 inner loop, Eq. 2)
 // One thread per sequence: the first rejected draft, the row that will be sampled from and how.
 __global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_max, int dense_q, float temperature,
-                                                         int eos_id, int emit_bonus, const float* __restrict__ u_accept,
+                                                         int eos_id, int emit_bonus, int filter_on,
+                                                         const float* __restrict__ u_accept,
                                                          SamplerBufs sb, int32_t* __restrict__ n_accepted,
                                                          int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
                                                          uint32_t* __restrict__ near_tie) {
@@ -344,7 +358,10 @@ __global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_ma
     const int r = r0 + i;
     const int x = p.row_target[r];
     float px;
-    if (temperature > 0.f) px = __expf(sb.z_target[r] * inv_temp - sb.row_lse[r]);
+    if (temperature > 0.f && filter_on)             // filtered target: zero outside the kept set, renormalised inside
+      px = filter_keeps(filter_key(sb.z_target[r]), x, sb.f_key[r], sb.f_idx[r])
+               ? __expf(sb.z_target[r] * inv_temp - sb.f_lse[r]) : 0.0f;
+    else if (temperature > 0.f) px = __expf(sb.z_target[r] * inv_temp - sb.row_lse[r]);
     else px = (x == sb.row_arg[r]) ? 1.0f : 0.0f;
     float rho = px;
     if (dense_q) {
@@ -393,7 +410,12 @@ __global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_ma
 template <typename Q>
 struct SampleRow {
   const float* z; const Q* q; double inv_T, mxp, mxq; int tgt, mode;
-  __device__ double e_p(int j) const { return exp((double)z[j] * inv_T - mxp); }
+  int filt, f_idx; uint32_t f_key;                   // top-k / top-p threshold of the row (filt == 0: none)
+  __device__ double e_p(int j) const {
+    const float zj = z[j];
+    if (filt && !filter_keeps(filter_key(zj), j, f_key, f_idx)) return 0.0;
+    return exp((double)zj * inv_T - mxp);
+  }
   __device__ double e_q(int j) const { return exp((double)to_f32<Q>(q[j]) - mxq); }
   // inv_sp, inv_sq: reciprocals of the normalisers
   __device__ double weight(int j, double inv_sp, double inv_sq, int mode_now) const {
@@ -406,9 +428,13 @@ struct SampleRow {
 
 template <typename Q>
 __device__ __forceinline__ SampleRow<Q> sample_row(int b, int V, const float* logit_base, int rows_are_selected,
-                                                   const Q* q_logits, float temperature, const SamplerBufs& sb) {
+                                                   const Q* q_logits, float temperature, int filter_on,
+                                                   const SamplerBufs& sb) {
   SampleRow<Q> r;
   r.mode = sb.sel_mode[b];
+  r.filt = filter_on;
+  r.f_key = filter_on ? sb.f_key[sb.sel_row[b]] : 0u;
+  r.f_idx = filter_on ? sb.f_idx[sb.sel_row[b]] : 0;
   r.z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
   r.q = (r.mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
   r.inv_T = 1.0 / (double)temperature;
@@ -428,11 +454,11 @@ __device__ __forceinline__ double block_sum_f64(double v, double* red) {     // 
 
 template <typename Q>
 __global__ void __launch_bounds__(256) sample_sum_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                         const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
+                                                         const Q* __restrict__ q_logits, float temperature, int filter_on, SamplerBufs sb) {
   __shared__ double red[4];
   const int c = blockIdx.x, b = blockIdx.y;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
   const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
   const int j0 = min(c * chunk, V), j1 = min(j0 + chunk, V);
   double sp = 0.0, sq = 0.0;
@@ -462,11 +488,11 @@ __device__ __forceinline__ void sample_totals(const SamplerBufs& sb, int b, doub
 // chunk masses of the residual (index 0) and of p itself (index 1, used when the residual is empty)
 template <typename Q>
 __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                          const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
+                                                          const Q* __restrict__ q_logits, float temperature, int filter_on, SamplerBufs sb) {
   __shared__ double red[4];
   const int c = blockIdx.x, b = blockIdx.y;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
   double sp, sq;
   sample_totals(sb, b, sp, sq);
   const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
@@ -486,7 +512,7 @@ __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __
 
 template <typename Q>
 __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                          const Q* __restrict__ q_logits, float temperature,
+                                                          const Q* __restrict__ q_logits, float temperature, int filter_on,
                                                           const float* __restrict__ u_sample, SamplerBufs sb,
                                                           const int32_t* __restrict__ n_accepted, int k_max,
                                                           int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
@@ -495,7 +521,7 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   __shared__ int s_i[2];
   const int b = blockIdx.x, tid = threadIdx.x;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
+  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
   double sp, sq;
   sample_totals(sb, b, sp, sq);
   // chunk level (every thread walks the 32 chunk masses: same result in all threads)
@@ -612,8 +638,8 @@ void launch_q_stats(const Plan& p, int M_max, int V, const void* q_logits, int q
   else hipLaunchKernelGGL(q_stats_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, V, (const bf16*)q_logits, sb);
 }
 void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles, bool dense_q, float temperature,
-                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, int32_t* n_accepted,
-                        int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
+                        int eos_id, int emit_bonus, const float* u_accept, const SamplerBufs& sb, const FilterArgs& filter,
+                        int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
   const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
   if (n_vtiles > 4 * kStatChunks) {
     hipLaunchKernelGGL(row_stats_fold_kernel, dim3((M_max + 31) / 32, kStatChunks), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb);
@@ -623,28 +649,30 @@ void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles
     hipLaunchKernelGGL(row_stats_kernel, dim3(M_max), dim3(256), 0, st, p, M_max, n_vtiles, inv_temp, sb, sb.part_max,
                        sb.part_sum, sb.part_arg);
   }
+  if (filter.on) launch_filter(p, M_max, temperature, filter, sb, st);      // needs row_max
   hipLaunchKernelGGL(accept_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, st, p, B, k_max, dense_q ? 1 : 0, temperature,
-                     eos_id, emit_bonus, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
+                     eos_id, emit_bonus, filter.on, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
 }
 template <typename Q>
 static void launch_sample_t(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const Q* q_logits,
-                            float temperature, const float* u_sample, const SamplerBufs& sb, const int32_t* n_accepted,
+                            float temperature, int filt, const float* u_sample, const SamplerBufs& sb, const int32_t* n_accepted,
                             int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
   const int sel = rows_are_selected ? 1 : 0;
-  hipLaunchKernelGGL(sample_sum_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
-  hipLaunchKernelGGL(sample_mass_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
-  hipLaunchKernelGGL(sample_pick_kernel<Q>, dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, u_sample, sb,
+  hipLaunchKernelGGL(sample_sum_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, sb);
+  hipLaunchKernelGGL(sample_mass_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, sb);
+  hipLaunchKernelGGL(sample_pick_kernel<Q>, dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, u_sample, sb,
                      n_accepted, k_max, out_tokens, n_emitted, near_tie);
 }
 void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
-                   int q_dtype, float temperature, const float* u_sample, const SamplerBufs& sb,
+                   int q_dtype, float temperature, bool filter_on, const float* u_sample, const SamplerBufs& sb,
                    const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
                    hipStream_t st) {
+  const int filt = filter_on ? 1 : 0;
   if (temperature == 0.f) return;                    // the scan already emitted the arg-max tokens
   if (q_logits && q_dtype == BS_BF16)
-    launch_sample_t<bf16>(B, k_max, V, logit_base, rows_are_selected, (const bf16*)q_logits, temperature, u_sample, sb,
+    launch_sample_t<bf16>(B, k_max, V, logit_base, rows_are_selected, (const bf16*)q_logits, temperature, filt, u_sample, sb,
                           n_accepted, out_tokens, n_emitted, near_tie, st);
   else
-    launch_sample_t<float>(B, k_max, V, logit_base, rows_are_selected, (const float*)q_logits, temperature, u_sample, sb,
+    launch_sample_t<float>(B, k_max, V, logit_base, rows_are_selected, (const float*)q_logits, temperature, filt, u_sample, sb,
                            n_accepted, out_tokens, n_emitted, near_tie, st);
 }

@@ -122,6 +122,15 @@ class Engine:
             B.bs_accept_resample_logits(self.ctx, n, vocab if vocab is not None else logits.shape[1], logits, *args)
         return out
 
+    def set_filter(self, top_k=0, top_p=1.0):
+        """Top-k / top-p filtering of the target distribution for the following accept steps (0 / 1.0: off).
+        bf16 models get the float32 logits scratch the filtered path needs, allocated on first use."""
+        on = top_k > 0 or top_p < 1.0
+        if on and self.desc["dtype"] == B.BS_BF16 and getattr(self, "_filter_logits", None) is None:
+            self._filter_logits = torch.empty(self.B_max * (self.k_max + 1), self.desc["vocab"], dtype=torch.float32,
+                                              device=self.device)
+        B.bs_set_filter(self.ctx, top_k, top_p, getattr(self, "_filter_logits", None) if on else None)
+
     def kv_commit(self, seq_slot, n_commit):
         B.bs_kv_commit(self.ctx, seq_slot.numel(), seq_slot, n_commit)
 
