@@ -284,7 +284,7 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   launch_attention_init(c->s, c->B_max, c->attn_scratch, (hipStream_t)stream);
   launch_clear_status(c->plan.status, (hipStream_t)stream);
   st = check_hip(c);
-  if (st != BS_OK) { delete c; return st; }
+  if (st != BS_OK) { bs_destroy(c); return st; }
   *out = c;
   return BS_OK;
 }
@@ -441,8 +441,8 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
   if (filter.on && V > kFilterMaxVocab) return fail(c, BS_ESHAPE, "accept_resample: top-k / top-p support at most 262136 vocabulary entries");
   if (filter.on && !given_logits && s.dtype == BS_BF16 && !c->filter_logits)
     return fail(c, BS_ESTATE, "accept_resample: top-k / top-p on a bf16 model need the logits scratch of bs_set_filter");
+  if (given_logits) launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, 0, 0, 0, st);
   if (given_logits) {
-    launch_plan(p, c->kv, B, k_max, V, nullptr, nullptr, draft_tokens, draft_len, false, 0, 0, 0, st);
     launch_logit_stats(p, M_max, V, given_logits, inv_temp, c->sb, st);
     n_vtiles = (V + 1023) / 1024;
     sample_base = given_logits;
@@ -463,6 +463,8 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
     }
   }
   filter.logits = sample_base;
+  // (Running these HBM-bound statistics on a second stream beside the MFMA-bound LM-head pass was measured: the
+  // step got 2 % slower, every kernel of the process paying about 1 us more once a second stream exists.)
   if (q_logits) launch_q_stats(p, M_max, V, q_logits, q_dtype, c->sb, st);
   launch_accept_scan(p, B, k_max, M_max, n_vtiles, q_logits != nullptr, temperature, eos_id, emit_bonus, u_accept, c->sb,
                      filter, n_accepted, out_tokens, n_emitted, near_tie, st);
