@@ -107,6 +107,7 @@ void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipS
 }
 
 // ------------------------------------------------------------------ MFMA kernel (bf16 models)
+constexpr int kOneRound = 512;    // workgroups that are certainly resident at once (256 CUs, up to two per CU)
 // Workgroup tile: BM = 32*MT rows x 4 waves x NT weight row tiles.  For SwiGLU NT == 2 and the two row
 // tiles of a wave are the gate rows and the matching up rows of the same 32 output features, so both
 // land in the same lane.  Grid: one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs,
@@ -122,12 +123,16 @@ template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
-                                                        int m_blocks, int n_blocks, int n_split) {
+                                                        int m_blocks, int n_blocks, int n_split, int defer_rows) {
   // accumulators hold C^T tiles (SWAP): a lane owns one activation row and, per group of four
   // registers, four consecutive output columns, so the epilogue stores 8 or 16 bytes per lane
   using G = MfmaGemm<MT, NT, true>;
   extern __shared__ __align__(16) char lds[];
-  const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
+  // The row count lives in device memory.  A launch that fits the chip in one round does not wait for it before
+  // its first loads (defer_rows): it reads and multiplies all M_max rows - those at or beyond the count are stale
+  // rows of the same buffer, each affecting only its own output row - and applies the count to the stores.  A
+  // many-round launch reads it first and skips the row blocks beyond it.
+  int M = (!defer_rows && n_rows_dev) ? min(*n_rows_dev, M_max) : M_max;
   // XCD-first decoding: the (split, N block, M block) space, M block fastest, is cut into 8 contiguous ranges,
   // one per XCD (workgroup ids are dealt round-robin to the XCDs)
   const int tiles = m_blocks * n_blocks, total = tiles * n_split;
@@ -172,6 +177,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
   const int kt0 = (int)((long)nk * split / n_split), kt1 = (int)((long)nk * (split + 1) / n_split);
   G::run(acc, op, kt0, kt1, lds);
+  if (defer_rows && n_rows_dev) M = min(*n_rows_dev, M_max);
 
   typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
@@ -223,7 +229,7 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   static bool attr_set = false;              // more than 64 KiB of dynamic LDS needs an opt-in (192-row tiles)
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
-                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split);
+                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split, total <= kOneRound ? 1 : 0);
 }
 
 
@@ -233,10 +239,10 @@ template <int EPI>
 __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                     const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                     const f16* __restrict__ Wp, void* __restrict__ out, int m_blocks,
-                                                    int n_blocks) {
+                                                    int n_blocks, int defer_rows) {
   using G = MfmaGemm8;
   extern __shared__ __align__(16) char lds[];
-  const int M = n_rows_dev ? min(*n_rows_dev, M_max) : M_max;
+  int M = (!defer_rows && n_rows_dev) ? min(*n_rows_dev, M_max) : M_max;     // see gemm_mfma_kernel
   const int total = m_blocks * n_blocks, per_xcd = (total + 7) / 8;
   const int id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if ((int)(blockIdx.x / 8) >= per_xcd || id >= total) return;
@@ -277,6 +283,7 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
     G::run(acc, op, 0, nk, lds);
+  if (defer_rows && n_rows_dev) M = min(*n_rows_dev, M_max);
 
   typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
@@ -322,7 +329,7 @@ static void launch_gemm8(const int32_t* n_rows_dev, int M_max, int N, int K, con
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm8_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm8_kernel<EPI>), dim3(grid), dim3(512), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
-                     (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks);
+                     (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, m_blocks * n_blocks <= kOneRound ? 1 : 0);
 }
 
 // The eight-wave kernel addresses both matrices with 32-bit byte offsets and pays off when 192-row blocks fit

@@ -20,10 +20,13 @@ template <int MT>
 __global__ void __launch_bounds__(256, (MT <= 2 ? 2 : 1))
 qkv_rope_kernel(Plan p, KvView kv, int M_max, int K, int Hq, int Hkv, const f16* __restrict__ A,
                 const f16* __restrict__ Wp, const float* __restrict__ cos_t, const float* __restrict__ sin_t,
-                f16* __restrict__ q_out, f16* __restrict__ k_pages, f16* __restrict__ v_pages, int m_blocks) {
+                f16* __restrict__ q_out, f16* __restrict__ k_pages, f16* __restrict__ v_pages, int m_blocks,
+                int defer_rows) {
   using G = MfmaGemm<MT, 1, true>;
   extern __shared__ __align__(16) char lds[];
-  const int M = min(p.n_rows[0], M_max);
+  // a one-round launch does not wait for the row count before its first loads: it multiplies all M_max rows (those
+  // beyond the count are stale rows, each affecting only its own output) and applies the count to the stores
+  int M = defer_rows ? M_max : min(p.n_rows[0], M_max);
   // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2): every XCD takes a contiguous range
   // of (head, M block) tiles, M block fastest, so a head's weights are fetched by one L2 only.
   const int total = m_blocks * (Hq + 2 * Hkv), per_xcd = (total + 7) / 8;
@@ -52,6 +55,7 @@ qkv_rope_kernel(Plan p, KvView kv, int M_max, int K, int Hq, int Hkv, const f16*
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mi][0][i] = 0.f;
   G::run(acc, op, 0, nk, lds);
+  if (defer_rows) M = min(p.n_rows[0], M_max);
 
   // ---- epilogue.  Accumulator register i of lane (ln, lg) in tile mi: row m0 + 32 mi + ln,
   // head column d = 32 wave + 8 (i / 4) + 4 lg + (i % 4).
@@ -129,7 +133,8 @@ void launch_t(const Shape& s, const Plan& p, const KvView& kv, int M_max, const 
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)qkv_rope_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
   const int grid = 8 * ((m_blocks * heads + 7) / 8);
   hipLaunchKernelGGL((qkv_rope_kernel<MT>), dim3(grid), dim3(256), lds, st, p, kv, M_max, s.d, s.Hq, s.Hkv,
-                     (const f16*)A, (const f16*)Wp, cos_t, sin_t, (f16*)q_out, (f16*)k_pages, (f16*)v_pages, m_blocks);
+                     (const f16*)A, (const f16*)Wp, cos_t, sin_t, (f16*)q_out, (f16*)k_pages, (f16*)v_pages, m_blocks,
+                     m_blocks * heads <= 512 ? 1 : 0);
 }
 }  // namespace
 
