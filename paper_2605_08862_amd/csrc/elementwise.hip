@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
                                                       const float* __restrict__ gain, T* __restrict__ out) {
   __shared__ float red[4];
   const int r = blockIdx.x;
-  if (r >= p.n_rows[0]) return;
+  const int n_rows = p.n_rows[0];                        // waited for only after the row's loads are in flight
   typedef float f4 __attribute__((ext_vector_type(4)));
   float* x = h + (size_t)r * d;
   const float* sl = slabs + (size_t)r * d;
@@ -75,6 +75,7 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
         for (int it = 0; it < NV; ++it) v[it] += t[u][it];
       }
   }
+  if (r >= n_rows) return;                               // rows beyond the count: loaded (in bounds), never stored
   float ss = 0.f;
 #pragma unroll
   for (int it = 0; it < NV; ++it) {
