@@ -407,13 +407,13 @@ __global__ void __launch_bounds__(64) accept_scan_kernel(Plan p, int B, int k_ma
 // Divisions by per-row constants (T, the two normalisers) are multiplications by their float64 reciprocals: a
 // float64 division costs about as much as the exponential next to it, and the one-ulp difference is far below
 // what the order of the running sums already leaves open.
-template <typename Q>
+template <typename Q, bool FILT>
 struct SampleRow {
   const float* z; const Q* q; double inv_T, mxp, mxq; int tgt, mode;
-  int filt, f_idx; uint32_t f_key;                   // top-k / top-p threshold of the row (filt == 0: none)
+  int f_idx; uint32_t f_key;                         // top-k / top-p threshold of the row (FILT only)
   __device__ double e_p(int j) const {
     const float zj = z[j];
-    if (filt && !filter_keeps(filter_key(zj), j, f_key, f_idx)) return 0.0;
+    if (FILT && !filter_keeps(filter_key(zj), j, f_key, f_idx)) return 0.0;
     return exp((double)zj * inv_T - mxp);
   }
   __device__ double e_q(int j) const { return exp((double)to_f32<Q>(q[j]) - mxq); }
@@ -426,15 +426,13 @@ struct SampleRow {
   }
 };
 
-template <typename Q>
-__device__ __forceinline__ SampleRow<Q> sample_row(int b, int V, const float* logit_base, int rows_are_selected,
-                                                   const Q* q_logits, float temperature, int filter_on,
-                                                   const SamplerBufs& sb) {
-  SampleRow<Q> r;
+template <typename Q, bool FILT>
+__device__ __forceinline__ SampleRow<Q, FILT> sample_row(int b, int V, const float* logit_base, int rows_are_selected,
+                                                         const Q* q_logits, float temperature, const SamplerBufs& sb) {
+  SampleRow<Q, FILT> r;
   r.mode = sb.sel_mode[b];
-  r.filt = filter_on;
-  r.f_key = filter_on ? sb.f_key[sb.sel_row[b]] : 0u;
-  r.f_idx = filter_on ? sb.f_idx[sb.sel_row[b]] : 0;
+  r.f_key = FILT ? sb.f_key[sb.sel_row[b]] : 0u;
+  r.f_idx = FILT ? sb.f_idx[sb.sel_row[b]] : 0;
   r.z = logit_base + (size_t)(rows_are_selected ? b : sb.sel_row[b]) * V;
   r.q = (r.mode == MODE_RESID_DENSE) ? q_logits + (size_t)sb.sel_qrow[b] * V : nullptr;
   r.inv_T = 1.0 / (double)temperature;
@@ -452,13 +450,13 @@ __device__ __forceinline__ double block_sum_f64(double v, double* red) {     // 
   return red[0] + red[1] + red[2] + red[3];
 }
 
-template <typename Q>
+template <typename Q, bool FILT>
 __global__ void __launch_bounds__(256) sample_sum_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                         const Q* __restrict__ q_logits, float temperature, int filter_on, SamplerBufs sb) {
+                                                         const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
   __shared__ double red[4];
   const int c = blockIdx.x, b = blockIdx.y;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
+  const SampleRow<Q, FILT> r = sample_row<Q, FILT>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
   const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
   const int j0 = min(c * chunk, V), j1 = min(j0 + chunk, V);
   double sp = 0.0, sq = 0.0;
@@ -486,13 +484,13 @@ __device__ __forceinline__ void sample_totals(const SamplerBufs& sb, int b, doub
 }
 
 // chunk masses of the residual (index 0) and of p itself (index 1, used when the residual is empty)
-template <typename Q>
+template <typename Q, bool FILT>
 __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                          const Q* __restrict__ q_logits, float temperature, int filter_on, SamplerBufs sb) {
+                                                          const Q* __restrict__ q_logits, float temperature, SamplerBufs sb) {
   __shared__ double red[4];
   const int c = blockIdx.x, b = blockIdx.y;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
+  const SampleRow<Q, FILT> r = sample_row<Q, FILT>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
   double sp, sq;
   sample_totals(sb, b, sp, sq);
   const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
@@ -510,9 +508,9 @@ __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __
   }
 }
 
-template <typename Q>
+template <typename Q, bool FILT>
 __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
-                                                          const Q* __restrict__ q_logits, float temperature, int filter_on,
+                                                          const Q* __restrict__ q_logits, float temperature,
                                                           const float* __restrict__ u_sample, SamplerBufs sb,
                                                           const int32_t* __restrict__ n_accepted, int k_max,
                                                           int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
@@ -521,7 +519,7 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   __shared__ int s_i[2];
   const int b = blockIdx.x, tid = threadIdx.x;
   if (sb.sel_mode[b] == MODE_NONE) return;
-  const SampleRow<Q> r = sample_row<Q>(b, V, logit_base, rows_are_selected, q_logits, temperature, filter_on, sb);
+  const SampleRow<Q, FILT> r = sample_row<Q, FILT>(b, V, logit_base, rows_are_selected, q_logits, temperature, sb);
   double sp, sq;
   sample_totals(sb, b, sp, sq);
   // chunk level (every thread walks the 32 chunk masses: same result in all threads)
@@ -653,26 +651,25 @@ void launch_accept_scan(const Plan& p, int B, int k_max, int M_max, int n_vtiles
   hipLaunchKernelGGL(accept_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, st, p, B, k_max, dense_q ? 1 : 0, temperature,
                      eos_id, emit_bonus, filter.on, u_accept, sb, n_accepted, out_tokens, n_emitted, near_tie);
 }
-template <typename Q>
+template <typename Q, bool FILT>
 static void launch_sample_t(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const Q* q_logits,
-                            float temperature, int filt, const float* u_sample, const SamplerBufs& sb, const int32_t* n_accepted,
+                            float temperature, const float* u_sample, const SamplerBufs& sb, const int32_t* n_accepted,
                             int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie, hipStream_t st) {
   const int sel = rows_are_selected ? 1 : 0;
-  hipLaunchKernelGGL(sample_sum_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, sb);
-  hipLaunchKernelGGL(sample_mass_kernel<Q>, dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, sb);
-  hipLaunchKernelGGL(sample_pick_kernel<Q>, dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, filt, u_sample, sb,
+  hipLaunchKernelGGL((sample_sum_kernel<Q, FILT>), dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
+  hipLaunchKernelGGL((sample_mass_kernel<Q, FILT>), dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
+  hipLaunchKernelGGL((sample_pick_kernel<Q, FILT>), dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, u_sample, sb,
                      n_accepted, k_max, out_tokens, n_emitted, near_tie);
 }
 void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
                    int q_dtype, float temperature, bool filter_on, const float* u_sample, const SamplerBufs& sb,
                    const int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted, uint32_t* near_tie,
                    hipStream_t st) {
-  const int filt = filter_on ? 1 : 0;
   if (temperature == 0.f) return;                    // the scan already emitted the arg-max tokens
-  if (q_logits && q_dtype == BS_BF16)
-    launch_sample_t<bf16>(B, k_max, V, logit_base, rows_are_selected, (const bf16*)q_logits, temperature, filt, u_sample, sb,
-                          n_accepted, out_tokens, n_emitted, near_tie, st);
-  else
-    launch_sample_t<float>(B, k_max, V, logit_base, rows_are_selected, (const float*)q_logits, temperature, filt, u_sample, sb,
-                           n_accepted, out_tokens, n_emitted, near_tie, st);
+  // the filtered kernels are instantiations of their own: the membership test costs the unfiltered path nothing
+#define BS_SAMPLE(Q_, F_) launch_sample_t<Q_, F_>(B, k_max, V, logit_base, rows_are_selected, (const Q_*)q_logits, temperature, \
+                                                  u_sample, sb, n_accepted, out_tokens, n_emitted, near_tie, st)
+  if (q_logits && q_dtype == BS_BF16) { if (filter_on) BS_SAMPLE(bf16, true); else BS_SAMPLE(bf16, false); }
+  else                                { if (filter_on) BS_SAMPLE(float, true); else BS_SAMPLE(float, false); }
+#undef BS_SAMPLE
 }
