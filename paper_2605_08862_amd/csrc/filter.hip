@@ -34,7 +34,7 @@ constexpr double kScale = 35184372088832.0;                  // 2^45: V < 2^18 t
 constexpr int kLevels = 3;
 __device__ __constant__ const int kBits[kLevels] = {11, 11, 10};
 
-constexpr int kCand = 5120;                                  // candidate list entries (LDS)
+constexpr int kCand = 2048;                                  // candidate list entries (LDS); three workgroups fit a CU
 constexpr int kIdxBits = 18, kLowBits = 21, kCompBits = kIdxBits + kLowBits;
 constexpr u64 kIdxMask = (1ull << kIdxBits) - 1;
 
@@ -54,23 +54,21 @@ __device__ __forceinline__ u64 composite(uint32_t key, int j) {
   return ((u64)(key & ((1u << kLowBits) - 1)) << kIdxBits) | (kIdxMask - (u64)j);
 }
 
-// f(j, z_j) for every token of the row; four 16-byte loads in flight per thread
+// f(j, z_j) for every token of the row; eight 16-byte loads in flight per thread (a workgroup per row is limited by
+// the bytes it keeps in flight, not by HBM)
 template <typename F>
 __device__ __forceinline__ void for_each_logit(const float* __restrict__ z, int V, F f) {
   const int tid = threadIdx.x;
   const int nvec = (((uintptr_t)z) & 15) == 0 ? V / 4 : 0;
   int i = tid;
-  for (; i + 768 < nvec; i += 1024) {
-    const f4 a = *(const f4*)(z + 4 * (size_t)i), b = *(const f4*)(z + 4 * (size_t)(i + 256));
-    const f4 c = *(const f4*)(z + 4 * (size_t)(i + 512)), d = *(const f4*)(z + 4 * (size_t)(i + 768));
+  for (; i + 7 * 256 < nvec; i += 8 * 256) {
+    f4 v[8];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) f(4 * i + e, a[e]);
+    for (int u = 0; u < 8; ++u) v[u] = *(const f4*)(z + 4 * (size_t)(i + u * 256));
 #pragma unroll
-    for (int e = 0; e < 4; ++e) f(4 * (i + 256) + e, b[e]);
+    for (int u = 0; u < 8; ++u)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) f(4 * (i + 512) + e, c[e]);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) f(4 * (i + 768) + e, d[e]);
+      for (int e = 0; e < 4; ++e) f(4 * (i + u * 256) + e, v[u][e]);
   }
   for (; i < nvec; i += 256) {
     const f4 a = *(const f4*)(z + 4 * (size_t)i);
@@ -185,11 +183,22 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
   auto mass = [&](float zj) -> u64 { return (u64)(exp((double)zj * inv_T - mxp) * kScale + 0.5); };
   auto value_of = [](uint32_t key) { return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key); };
 
+  // State of the two descents.  The short way below fills it in; where a bin is too large for the candidate list
+  // it leaves the descent at the level it reached and the long way (one row pass per level) continues from there.
+  uint32_t kk = 0;                                           // top-k threshold: ranking key and index cut
+  int cut_k = INT_MAX;
+  bool k_known = !use_k;
+  uint32_t k_prefix = 0, k_need = (uint32_t)top_k;           // top-k descent: key bits found, tokens still to take
+  int k_done = 0, k_lvl = 0;
+  uint32_t prefix = 0;                                       // mass descent: key bits found, mass still to reach
+  int done = 0, m_lvl = 0, cut = INT_MAX;
+  u64 target = 0, kept_mass = 0;
+  bool finished = false;
+
   // ================= short way: first level from the row, the rest from a candidate list in LDS
   {
     bool ok = true;
     int b1 = -1;                                             // first-level bin of the top-k threshold (-1: no top-k)
-    uint32_t need1 = 0;
     if (use_k) {
       for (int i = tid; i < 2048; i += 256) sh.hist_c[i] = 0;
       __syncthreads();
@@ -197,7 +206,10 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
       __syncthreads();
       find_crossing(sh.hist_c, 2048, (u64)top_k, sh);
       b1 = max(sh.bin, 0);
-      need1 = (uint32_t)top_k - (uint32_t)sh.above;
+      k_need = (uint32_t)top_k - (uint32_t)sh.above;
+      k_prefix = (uint32_t)b1;
+      k_done = kBits[0];
+      k_lvl = 1;
       ok = sh.hist_c[b1] <= (uint32_t)kCand;
       __syncthreads();
     }
@@ -223,8 +235,11 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
       int n_list = 0;
       if (use_k) {
         n_list = min(sh.cand_n, kCand);
-        c_k = list_select(sh, n_list, 0, (u64)need1, [](u64) -> u64 { return 1; });
+        c_k = list_select(sh, n_list, 0, (u64)k_need, [](u64) -> u64 { return 1; });
         const uint32_t hi = (uint32_t)b1 << kLowBits;
+        kk = hi | (uint32_t)(c_k >> kIdxBits);
+        cut_k = (int)(kIdxMask - (c_k & kIdxMask));
+        k_known = true;
         for (int i = tid; i < n_list; i += 256) {
           const u64 c = sh.cand[i];
           if (c >= c_k) atomicAdd(&sh.hist_m[b1], mass(value_of(hi | (uint32_t)(c >> kIdxBits))));
@@ -239,18 +254,21 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
       __syncthreads();
       const u64 total = sh.above;
       __syncthreads();
-      int bf = b1;                                           // first-level bin and composite of the final threshold
-      u64 c_f = c_k, kept = total;
-      if (use_p) {
+      if (!use_p) {
+        prefix = kk; cut = cut_k; kept_mass = total; finished = true;
+      } else {
         const double td = (double)top_p * (double)total;
-        u64 target = (u64)td;
+        target = (u64)td;
         if ((double)target < td) ++target;
         if (target < 1) target = 1;
         if (target > total) target = total;
         find_crossing(sh.hist_m, 2048, target, sh);
-        bf = max(sh.bin, 0);
-        const u64 above1 = sh.above;
-        target -= above1;
+        const int bf = max(sh.bin, 0);                       // first-level bin of the final threshold
+        target -= sh.above;
+        kept_mass = sh.above;
+        prefix = (uint32_t)bf;
+        done = kBits[0];
+        m_lvl = 1;
         __syncthreads();
         if (bf != b1) {                                      // another bin: its tokens are all in the top-k set
           ok = sh.hist_c[bf] <= (uint32_t)kCand;
@@ -272,59 +290,45 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
         }
         if (ok) {
           const uint32_t hi = (uint32_t)bf << kLowBits;
-          c_f = list_select(sh, n_list, c_k, target, [&](u64 c) -> u64 { return mass(value_of(hi | (uint32_t)(c >> kIdxBits))); });
-          kept = above1 + sh.above + mass(value_of(hi | (uint32_t)(c_f >> kIdxBits)));
+          const u64 c_f = list_select(sh, n_list, c_k, target, [&](u64 c) -> u64 { return mass(value_of(hi | (uint32_t)(c >> kIdxBits))); });
+          prefix = hi | (uint32_t)(c_f >> kIdxBits);
+          cut = (int)(kIdxMask - (c_f & kIdxMask));
+          kept_mass += sh.above + mass(value_of(prefix));
+          finished = true;
           __syncthreads();
         }
-      }
-      if (ok) {
-        if (tid == 0) {
-          sb.f_key[m] = ((uint32_t)bf << kLowBits) | (uint32_t)(c_f >> kIdxBits);
-          sb.f_idx[m] = (int)(kIdxMask - (c_f & kIdxMask));
-          sb.f_lse[m] = (float)(mxp + log((double)kept / kScale));
-        }
-        return;
       }
     }
     __syncthreads();
   }
 
-  // ================= long way: every level reads the row
-
-  // ---- top-k: key of the k-th token of the ranking and the index cut among its equals
-  uint32_t kk = 0;
-  int cut_k = INT_MAX;
-  if (use_k) {
-    uint32_t prefix = 0, need = (uint32_t)top_k, eq = 0;
-    int done = 0;
-    for (int lvl = 0; lvl < kLevels; ++lvl) {
-      const int bits = kBits[lvl], nb = 1 << bits, shift = 32 - done - bits;
+  // ================= long way: every remaining level reads the row
+  if (!k_known) {
+    uint32_t eq = 0;
+    for (int lvl = k_lvl; lvl < kLevels; ++lvl) {
+      const int bits = kBits[lvl], nb = 1 << bits, shift = 32 - k_done - bits;
       for (int i = tid; i < nb; i += 256) sh.hist_c[i] = 0;
       __syncthreads();
       for_each_logit(z, V, [&](int, float zj) {
         const uint32_t key = filter_key(zj);
-        if (done == 0 || (key >> (32 - done)) == prefix) atomicAdd(&sh.hist_c[(key >> shift) & (nb - 1)], 1u);
+        if (k_done == 0 || (key >> (32 - k_done)) == k_prefix) atomicAdd(&sh.hist_c[(key >> shift) & (nb - 1)], 1u);
       });
       __syncthreads();
-      find_crossing(sh.hist_c, nb, need, sh);
-      const int bin = max(sh.bin, 0);                      // a crossing always exists: need <= tokens under the prefix
-      need -= (uint32_t)sh.above;
-      prefix = (prefix << bits) | (uint32_t)bin;
+      find_crossing(sh.hist_c, nb, k_need, sh);
+      const int bin = max(sh.bin, 0);                      // a crossing always exists: k_need <= tokens under the prefix
+      k_need -= (uint32_t)sh.above;
+      k_prefix = (k_prefix << bits) | (uint32_t)bin;
       eq = sh.hist_c[bin];
-      done += bits;
+      k_done += bits;
       __syncthreads();
     }
-    kk = prefix;
-    if (eq > need) cut_k = nth_match(z, V, (int)need, [&](int, float zj) { return filter_key(zj) == kk; }, sh);
+    kk = k_prefix;
+    if (eq > k_need) cut_k = nth_match(z, V, (int)k_need, [&](int, float zj) { return filter_key(zj) == kk; }, sh);
   }
   auto in_topk = [&](uint32_t key, int j) { return !use_k || filter_keeps(key, j, kk, cut_k); };
 
   // ---- mass of the top-k set and, with top-p, the shortest prefix of it that reaches top_p of that mass
-  uint32_t prefix = 0;
-  int done = 0, cut = cut_k;
-  u64 target = 0, kept_mass = 0;
-  bool finished = false;
-  for (int lvl = 0; lvl < kLevels && !finished; ++lvl) {
+  for (int lvl = m_lvl; lvl < kLevels && !finished; ++lvl) {
     const int bits = kBits[lvl], nb = 1 << bits, shift = 32 - done - bits;
     for (int i = tid; i < nb; i += 256) sh.hist_m[i] = 0;
     __syncthreads();
@@ -344,7 +348,7 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
       __syncthreads();
       const u64 total = sh.above;
       __syncthreads();
-      if (!use_p) { kept_mass = total; prefix = kk; finished = true; continue; }
+      if (!use_p) { kept_mass = total; prefix = kk; cut = cut_k; finished = true; continue; }
       const double td = (double)top_p * (double)total;
       target = (u64)td;
       if ((double)target < td) ++target;
@@ -360,9 +364,7 @@ __global__ void __launch_bounds__(256) filter_kernel(Plan p, int M_max, int V, c
     if (lvl == kLevels - 1) {
       // all tokens of this bin have the same logit, hence the same mass q_e: ceil(target / q_e) of them are kept
       const u64 bin_mass = sh.hist_m[bin];
-      float zt;
-      { const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix; zt = __uint_as_float(u); }
-      u64 q_e = mass(zt);
+      u64 q_e = mass(value_of(prefix));
       if (q_e == 0) q_e = 1;                               // not reached: the bin holds mass
       const u64 n_eq = bin_mass / q_e, n_need = (target + q_e - 1) / q_e;
       kept_mass += n_need * q_e;
