@@ -17,13 +17,13 @@
 // which (the lowest indices) by a counting pass that runs only when not all of them are kept.
 // The mass of the kept set (for the renormalisation in the accept test) comes out of the same integers.
 //
-// Reading a 600 KB row once per level (up to eight times) is the whole cost, so the common case takes a shorter
-// way with the same result: after the first level of a descent, the tokens of the one bin that holds the
-// threshold are copied to a list in LDS (as 39-bit composites: the 21 key bits below the bin, then the inverted
-// index, so that no two are equal and ties need no special case) and the remaining levels walk that list.  The
-// first pass of the mass descent doubles as the list-building pass of top-k, so a row is read two or three times.
-// A bin with more tokens than the list holds (a constant row, heavily quantised logits) falls back to the
-// level-by-level passes.
+// Reading a 600 KB row once per level (up to eight times) would be the whole cost, so after the first level of a
+// descent the tokens of the one bin that holds the threshold are copied to a list in LDS (as 39-bit composites: the
+// 21 key bits below the bin, then the inverted index, so that no two are equal and ties need no special case) and
+// the remaining levels walk that list.  The first pass of the mass descent doubles as the list-building pass of
+// top-k, so a row is read two or three times.  Where a bin holds more tokens than the list (a constant row,
+// heavily quantised logits, the nucleus boundary of a flat row) the descent goes on from the level it has reached
+// with one pass over the row per level.
 #include "common.h"
 #include <limits.h>
 
