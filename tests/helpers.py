@@ -68,8 +68,9 @@ def compare_sampler(gpu, logits_rows, draft_tokens, draft_len, u_accept, u_sampl
 
 
 def device_kept(z_row_f32, f_key, f_idx):
-    """Indices a device threshold (ranking key, index cut) keeps in a float32 logits row: decodes the encoding
-    documented in include/bubblespec.h's debug hook (unsigned order of the key == numeric order, -0 == +0)."""
+    """Indices a device threshold (ranking key, index cut) keeps in a float32 logits row.  The key is the float's
+    bit pattern made monotone (sign bit set for non-negative values, all bits inverted for negative ones, -0 == +0):
+    token j is kept iff key_j > f_key, or key_j == f_key and j <= f_idx."""
     z = np.ascontiguousarray(z_row_f32, dtype=np.float32) + np.float32(0.0)
     u = z.view(np.uint32).astype(np.int64)
     key = np.where(u & 0x80000000, (~u) & 0xffffffff, u | 0x80000000)
