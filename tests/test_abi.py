@@ -51,4 +51,12 @@ def test_null_arguments_are_rejected(lib):
     assert lib.bs_verify_step(None, 1, None, None, None, None, 0, None, None) == B.BS_EINVAL
     assert lib.bs_kv_commit(None, 1, None, None, None) == B.BS_EINVAL
     assert lib.bs_draft_lookup(None, 1, None, None, 4, 1, 4, None, None, None) == B.BS_EINVAL
+    assert lib.bs_set_filter(None, 5, 0.9, None) == B.BS_EINVAL
     assert lib.bs_last_error(None) == b"null context"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
