@@ -367,14 +367,24 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   static const char* env_nt = getenv("BS_GEMM_NT");
   static const char* env_mt = getenv("BS_GEMM_MT");
   static const char* env_g8 = getenv("BS_GEMM8");
+  bool small_tiles = false;
   if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE) {
-    const bool want = env_g8 ? atoi(env_g8) != 0 : (EPI == EPI_SWIGLU);
+    bool want = env_g8 ? atoi(env_g8) != 0 : (EPI == EPI_SWIGLU);
+    if (EPI == EPI_SWIGLU && !env_g8 && !env_mt && M_max > 128) {
+      // 192-row tiles, one workgroup per CU, against 96-row tiles, two per CU (about 10 % slower per unit of work):
+      // whichever needs fewer rounds of the 256 CUs.  288 rows x 18944 features: 2 x 148 workgroups are two rounds,
+      // 3 x 148 of the small ones fit at once (measured: 133 -> 96 us).
+      const int nb = (N + 127) / 128;
+      const long cost6 = (long)(((M_max + 191) / 192 * nb + 255) / 256) * 60;
+      const long cost3 = (long)(((M_max + 95) / 96 * nb + 511) / 512) * 66;
+      if (cost3 < cost6) { want = false; small_tiles = true; }
+    }
     if (want && gemm8_applies(M_max, N, K, EPI == EPI_SWIGLU ? 2 * N : N)) {
       launch_gemm8<EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
       return 1;
     }
   }
-  int mt = pick_mt(M_max);
+  int mt = small_tiles ? 3 : pick_mt(M_max);
   // float32-epilogue GEMMs have narrow outputs (N = d or Nqkv): measured on MI355X at M = 576, smaller row
   // tiles with at most 4 K splits beat 192-row tiles with 7 splits (down projection 50 -> 33 us, O 17 -> 13 us)
   if ((EPI == EPI_RESID_ADD || EPI == EPI_STORE_F32) && M_max > 64) mt = (K / kBK <= 32) ? 2 : 4;
