@@ -236,7 +236,7 @@ bs_status bs_kv_read(bs_ctx* ctx, int layer, int slot, int pos0, int n, void* k_
  * Errors: BS_EINVAL (null, unknown class), BS_EHIP. */
 enum {
   BS_PROF_NONE = 0,
-  BS_PROF_ATTENTION = 1,   /* ragged verify attention (bf16 models: the MFMA kernel, merge excluded) */
+  BS_PROF_ATTENTION = 1,   /* ragged verify attention (bf16 models: the MFMA kernel, which also merges the token chunks) */
   BS_PROF_GEMM_QKV = 2,    /* QKV projection (bf16 models with head size 128: the kernel that also applies the
                               rotary embedding and appends K/V) */
   BS_PROF_GEMM_O = 3,
