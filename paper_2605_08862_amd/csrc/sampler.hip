@@ -308,10 +308,12 @@ __global__ void __launch_bounds__(256) q_stats_kernel(Plan p, int V, const Q* __
   const bool aligned = (((uintptr_t)q) & 15) == 0;
   const int nvec = aligned ? V / N : 0;
   int i = tid;
-  for (; i + 768 < nvec; i += 1024) {                  // four vectors in flight per thread
-    const u32x4 r0 = *(const u32x4*)(q + (size_t)i * N), r1 = *(const u32x4*)(q + (size_t)(i + 256) * N);
-    const u32x4 r2 = *(const u32x4*)(q + (size_t)(i + 512) * N), r3 = *(const u32x4*)(q + (size_t)(i + 768) * N);
-    absorb_vec(r0); absorb_vec(r1); absorb_vec(r2); absorb_vec(r3);
+  for (; i + 7 * 256 < nvec; i += 8 * 256) {           // eight vectors in flight per thread: with one workgroup per
+    u32x4 r[8];                                        // row (two per CU) the bytes in flight, not HBM, set the rate
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r[u] = *(const u32x4*)(q + (size_t)(i + u * 256) * N);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) absorb_vec(r[u]);
   }
   for (; i < nvec; i += 256) absorb_vec(*(const u32x4*)(q + (size_t)i * N));
   for (int n = nvec * N + tid; n < V; n += 256) absorb(to_f32<Q>(q[n]));
