@@ -211,11 +211,26 @@ __global__ void __launch_bounds__(256) row_stats_fold_kernel(Plan p, int M_max, 
     if (m2 > mx) { sum = sum * __expf((mx - m2) * inv_temp) + s2; mx = m2; arg = a2; }
     else if (m2 > -INFINITY) { sum += s2 * __expf((m2 - mx) * inv_temp); if (m2 == mx && a2 < arg) arg = a2; }
   };
-  if (valid)
-    for (int vt = v0 + vl; vt < v1; vt += 8) {
+  if (valid) {
+    // four tile entries are requested before the first is folded (same order of folding): one memory round trip
+    // per four entries instead of one per entry
+    int vt = v0 + vl;
+    for (; vt + 24 < v1; vt += 32) {
+      float m4[4], s4[4];
+      int a4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t o = (size_t)(vt + 8 * u) * M_max + r;
+        m4[u] = sb.part_max[o]; s4[u] = sb.part_sum[o]; a4[u] = sb.part_arg[o];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) fold(m4[u], s4[u], a4[u]);
+    }
+    for (; vt < v1; vt += 8) {
       const size_t o = (size_t)vt * M_max + r;
       fold(sb.part_max[o], sb.part_sum[o], sb.part_arg[o]);
     }
+  }
   s_mx[vl][rr] = mx; s_sum[vl][rr] = sum; s_arg[vl][rr] = arg;
   __syncthreads();
   if (vl == 0 && valid) {
