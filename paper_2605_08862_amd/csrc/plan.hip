@@ -14,15 +14,18 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   __shared__ int s_fault;
   __shared__ int s_slot[4096];                      // B <= 4096 (checked at context creation)
   __shared__ int s_k[4096];                         // validated k_b (-1: skipped)
+  __shared__ int s_c[4096];                         // c_b
   __shared__ int s_pr[256], s_pt[256];              // per-thread partial row / draft counts, then their prefix
   const int tid = threadIdx.x;
   if (tid == 0) s_fault = 0;
   if (need_kv)
     for (int b = tid; b < B; b += blockDim.x) s_slot[b] = seq_slot[b];
   __syncthreads();
-  // phase 1: per-sequence validation (parallel over sequences).  Global loads are requested eight at a time:
-  // one dependent load per loop iteration made this kernel latency-bound (33 pages per sequence at context 2048).
-  for (int b = tid; b < B; b += blockDim.x) {
+  // phase 1: per-sequence validation.  Four lanes share a sequence: each repeats the scalar checks (same addresses:
+  // one transaction) and takes a quarter of the duplicate-slot scan and of the block-table entries, eight loads at a
+  // time, so that a context of 2048 tokens (33 pages) costs two memory round trips instead of five.
+  for (int b = tid >> 2; b < B; b += blockDim.x >> 2) {
+    const int sub = tid & 3;
     int k = draft_len[b], fault = 0, c = 0, slot = 0;
     if (k < 0 || k > k_max) { fault |= BS_FAULT_DRAFT_LEN; }
     if (need_kv) {
@@ -30,7 +33,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
       if (slot < 0 || slot >= kv.n_slots) {
         fault |= BS_FAULT_SLOT;
       } else {
-        for (int b2 = 0; b2 < b; ++b2) if (s_slot[b2] == slot) fault |= BS_FAULT_SLOT;
+        for (int b2 = sub; b2 < b; b2 += 4) if (s_slot[b2] == slot) fault |= BS_FAULT_SLOT;
         c = kv.ctx_len[slot];
         if (!(fault & BS_FAULT_DRAFT_LEN)) {
           if (c < 0 || (long)c + k + 1 > (long)kv.max_pages * kPage) {
@@ -38,7 +41,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
           } else {
             const int32_t* bt = kv.block_table + (size_t)slot * kv.max_pages;
             const int last = (c + k) / kPage;
-            for (int pg0 = 0; pg0 <= last; pg0 += 8) {
+            for (int pg0 = sub * 8; pg0 <= last; pg0 += 32) {
               int id[8];
 #pragma unroll
               for (int u = 0; u < 8; ++u) id[u] = bt[min(pg0 + u, last)];
@@ -49,11 +52,16 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
         }
       }
     }
-    p.seq_k[b] = fault ? -1 : k;
-    s_k[b] = fault ? -1 : k;
-    p.seq_c[b] = c;
-    p.seq_slot[b] = slot;
-    if (fault) atomicOr(&s_fault, fault);
+    fault |= __shfl_xor(fault, 1);
+    fault |= __shfl_xor(fault, 2);
+    if (sub == 0) {
+      p.seq_k[b] = fault ? -1 : k;
+      s_k[b] = fault ? -1 : k;
+      s_c[b] = c;
+      p.seq_c[b] = c;
+      p.seq_slot[b] = slot;
+      if (fault) atomicOr(&s_fault, fault);
+    }
   }
   __syncthreads();
   // phase 2: prefix sums over the sequences (each thread a contiguous range, partials scanned by thread 0)
@@ -86,7 +94,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   // phase 3: per-row maps (parallel over sequences x positions)
   for (int idx = tid; idx < B * (k_max + 1); idx += blockDim.x) {
     int b = idx / (k_max + 1), i = idx % (k_max + 1);
-    int k = p.seq_k[b];
+    int k = s_k[b];
     if (k < 0 || i > k) continue;
     int r = p.row_start[b] + i;
     int tok = (i == 0) ? (last_token ? last_token[b] : 0) : draft_tokens[(size_t)b * k_max + i - 1];
@@ -116,7 +124,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   // sum_b chunks(b) <= B + T / chunk <= B + 4 S0 always (the work list's capacity).
   __shared__ int s_red[256];
   __shared__ int s_cht;
-  auto tiles_of = [&](int b) { return s_k[b] < 0 ? 0 : (p.seq_c[b] + s_k[b] + 1 + kTile - 1) / kTile; };
+  auto tiles_of = [&](int b) { return s_k[b] < 0 ? 0 : (s_c[b] + s_k[b] + 1 + kTile - 1) / kTile; };
   {
     int t = 0, mx = 0, nv = 0;
     for (int b = b_lo; b < b_hi; ++b) { const int n = tiles_of(b); t += n; mx = max(mx, n); nv += n > 0; }
