@@ -371,12 +371,14 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE) {
     bool want = env_g8 ? atoi(env_g8) != 0 : (EPI == EPI_SWIGLU);
     if (EPI == EPI_SWIGLU && !env_g8 && !env_mt && M_max > 128) {
-      // 192-row tiles, one workgroup per CU, against 96-row tiles, two per CU (about 10 % slower per unit of work):
-      // whichever needs fewer rounds of the 256 CUs.  288 rows x 18944 features: 2 x 148 workgroups are two rounds,
-      // 3 x 148 of the small ones fit at once (measured: 133 -> 96 us).
+      // 192-row tiles, one workgroup per CU, against 96-row tiles, two per CU: whichever needs less time by rounds of
+      // the 256 CUs.  In a single round the small tiles are about 10 % slower per unit of work; over several rounds
+      // they are faster, because one workgroup's pipeline fill and epilogue overlap the other's main loop.
+      // Measured, 7B shape (18944 features): 288 rows, 2 x 148 workgroups = two rounds against 3 x 148 small ones at
+      // once: 133 -> 96 us; 1152 rows, 3.5 rounds either way: 308 -> 290 us.
       const int nb = (N + 127) / 128;
-      const long cost6 = (long)(((M_max + 191) / 192 * nb + 255) / 256) * 60;
-      const long cost3 = (long)(((M_max + 95) / 96 * nb + 511) / 512) * 66;
+      const long r6 = ((M_max + 191) / 192 * nb + 255) / 256, r3 = ((M_max + 95) / 96 * nb + 511) / 512;
+      const long cost6 = r6 * 60, cost3 = r3 * (r3 > 1 ? 57 : 66);
       if (cost3 < cost6) { want = false; small_tiles = true; }
     }
     if (want && gemm8_applies(M_max, N, K, EPI == EPI_SWIGLU ? 2 * N : N)) {
