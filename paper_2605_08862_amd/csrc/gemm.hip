@@ -394,7 +394,16 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   const int m_blocks = (M_max + mt * 32 - 1) / (mt * 32);
   int nt = 2;
   if (EPI != EPI_SWIGLU) {
-    const int blocks2 = m_blocks * ((N + 255) / 256);
+    // 256-column tiles (two weight row tiles per wave: half the LDS reads per MFMA) if they can fill the chip, for
+    // the float32 epilogues with the help of two K splits (more slabs would cost the consumer more than the tiles
+    // gain; 7B shape, 1152 rows, down projection: 126 tiles x 2 splits take 147 us, 252 tiles of 128 columns 172 us)
+    int blocks2 = m_blocks * ((N + 255) / 256);
+    if (EPI == EPI_RESID_ADD || EPI == EPI_STORE_F32) {
+      int s2 = (256 + blocks2 / 2) / blocks2;
+      if (s2 > K / kBK / 4) s2 = K / kBK / 4;
+      if (s2 > 2) s2 = 2;
+      if (s2 > 1) blocks2 *= s2;
+    }
     if (blocks2 < 200) nt = 1;
     if (env_nt) nt = atoi(env_nt) == 1 ? 1 : 2;
   }
