@@ -31,7 +31,7 @@ AGREEMENT_NOISE = 0.771          # s with 2*Phi(-s/2) = 0.7 (lognormal closed fo
 # HBM bytes per launch of each kernel class at the DEFAULT workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a plain copy of known size; see profiles/bench_s1p5b_b64_c2048_k8_kernels.txt).  Other workloads: null.
 MEASURED_TRAFFIC_BYTES = {"gemm_gate_up": 69.3e6 + 10.3e6, "gemm_down": 48.3e6 + 14.2e6, "attention": 138.3e6 + 1.6e6,
-                          "lmhead": 649.7e6 + 23.7e6, "gemm_qkv": 19.7e6 + 2.2e6, "gemm_o": 13.8e6 + 5.2e6}
+                          "lmhead": 644.3e6 + 23.7e6, "gemm_qkv": 19.7e6 + 2.2e6, "gemm_o": 13.8e6 + 5.2e6}
 
 
 def build_workload(args):
