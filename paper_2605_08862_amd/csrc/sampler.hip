@@ -428,18 +428,23 @@ template <typename Q, bool FILT>
 struct SampleRow {
   const float* z; const Q* q; double inv_T, mxp, mxq; int tgt, mode;
   int f_idx; uint32_t f_key;                         // top-k / top-p threshold of the row (FILT only)
-  __device__ double e_p(int j) const {
-    const float zj = z[j];
+  // the *_v forms take the logits as values (callers that request many loads before using the first)
+  __device__ double e_p_v(int j, float zj) const {
     if (FILT && !filter_keeps(filter_key(zj), j, f_key, f_idx)) return 0.0;
     return exp((double)zj * inv_T - mxp);
   }
-  __device__ double e_q(int j) const { return exp((double)to_f32<Q>(q[j]) - mxq); }
+  __device__ double e_q_v(float qj) const { return exp((double)qj - mxq); }
+  __device__ double e_p(int j) const { return e_p_v(j, z[j]); }
+  __device__ double e_q(int j) const { return e_q_v(to_f32<Q>(q[j])); }
   // inv_sp, inv_sq: reciprocals of the normalisers
-  __device__ double weight(int j, double inv_sp, double inv_sq, int mode_now) const {
-    const double pj = e_p(j) * inv_sp;
+  __device__ double weight_v(int j, float zj, float qj, double inv_sp, double inv_sq, int mode_now) const {
+    const double pj = e_p_v(j, zj) * inv_sp;
     if (mode_now == MODE_PLAIN) return pj;
     if (mode_now == MODE_RESID_ONEHOT) return j == tgt ? 0.0 : pj;
-    return fmax(0.0, pj - e_q(j) * inv_sq);
+    return fmax(0.0, pj - e_q_v(qj) * inv_sq);
+  }
+  __device__ double weight(int j, double inv_sp, double inv_sq, int mode_now) const {
+    return weight_v(j, z[j], (mode_now == MODE_RESID_DENSE) ? to_f32<Q>(q[j]) : 0.f, inv_sp, inv_sq, mode_now);
   }
 };
 
@@ -565,8 +570,28 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   const int c0 = min(cs * chunk, V), c1 = min(c0 + chunk, V);
   const int slice = (c1 - c0 + 255) / 256;
   const int j0 = min(c0 + tid * slice, c1), j1 = min(j0 + slice, c1);
+  // One workgroup per sequence: nothing hides a load's latency here, so a thread requests its whole slice (up to
+  // kW logits of p and q) at once and keeps the weights in registers for the walk below.
+  constexpr int kW = 24;
+  const bool in_regs = slice <= kW;
+  double wv[kW];
   double csum = 0.0;
-  for (int j = j0; j < j1; ++j) csum += r.weight(j, sp, sq, mode);
+  if (in_regs) {
+    float zr[kW], qr[kW];
+#pragma unroll
+    for (int i = 0; i < kW; ++i) {
+      const int jj = min(j0 + i, V - 1);
+      zr[i] = r.z[jj];
+      qr[i] = (mode == MODE_RESID_DENSE) ? to_f32<Q>(r.q[jj]) : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < kW; ++i) {
+      wv[i] = (j0 + i < j1) ? r.weight_v(j0 + i, zr[i], qr[i], sp, sq, mode) : 0.0;
+      csum += wv[i];
+    }
+  } else {
+    for (int j = j0; j < j1; ++j) csum += r.weight(j, sp, sq, mode);
+  }
   s_scan[tid] = csum;
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {
@@ -587,11 +612,25 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   if (tid != owner) return;
   double acc = excl, w = 0.0, last_hi = 0.0, last_w = 0.0;
   int tok = -1, last = -1;
-  for (int j = j0; j < j1; ++j) {
-    w = r.weight(j, sp, sq, mode);
-    acc += w;
-    if (w > 0.0) { last = j; last_hi = acc; last_w = w; }
-    if (acc > t) { tok = j; break; }
+  if (in_regs) {
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < kW; ++i) {
+      const int j = j0 + i;
+      if (!found && j < j1) {
+        w = wv[i];
+        acc += w;
+        if (w > 0.0) { last = j; last_hi = acc; last_w = w; }
+        if (acc > t) { tok = j; found = true; }
+      }
+    }
+  } else {
+    for (int j = j0; j < j1; ++j) {
+      w = r.weight(j, sp, sq, mode);
+      acc += w;
+      if (w > 0.0) { last = j; last_hi = acc; last_w = w; }
+      if (acc > t) { tok = j; break; }
+    }
   }
   if (tok < 0) { tok = last; acc = last_hi; w = last_w; }
   const int n_acc = n_accepted[b];
