@@ -80,8 +80,11 @@ __global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const
     const bool valid = m < M;
     if (STATS) {
       const int tgt = valid ? row_target[m] : -1;
-      float mx = -INFINITY;
+      float mx = -INFINITY, zt = 0.f;
       int arg = 0x7fffffff;
+      bool hit = false;
+      // no store inside this loop: the draft token's logit is picked up by a select (a conditional store at each of
+      // the 32 positions cost 13 us of the 277 us launch)
 #pragma unroll
       for (int ni = 0; ni < kLmNT; ++ni)
 #pragma unroll
@@ -90,10 +93,19 @@ __global__ void __launch_bounds__(256, (kLmMT <= 3 ? 2 : 1)) lmhead_kernel(const
           const float z = acc[mi][ni][i];
           if (n < V) {
             if (z > mx) { mx = z; arg = n; }
-            if (valid && n == tgt) sb.z_target[m] = z;
-            if (valid && store && !store_vec) store[(size_t)m * V + n] = z;
+            if (n == tgt) { zt = z; hit = true; }
           }
         }
+      if (hit) sb.z_target[m] = zt;                    // tgt >= 0 only for valid rows
+      if (valid && store && !store_vec) {
+#pragma unroll
+        for (int ni = 0; ni < kLmNT; ++ni)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int n = n_wave0 + ni * 32 + acc_row(lane, i);
+            if (n < V) store[(size_t)m * V + n] = acc[mi][ni][i];
+          }
+      }
       if (valid && store && store_vec) {
         // registers 4 i4 .. 4 i4 + 3 of a lane are four consecutive vocabulary entries: 16-byte stores
 #pragma unroll
