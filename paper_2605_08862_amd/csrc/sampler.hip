@@ -542,14 +542,15 @@ __global__ void __launch_bounds__(256) sample_mass_kernel(int V, const float* __
   }
 }
 
+constexpr int kPickThreads = 1024;
 template <typename Q, bool FILT>
-__global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
+__global__ void __launch_bounds__(kPickThreads) sample_pick_kernel(int V, const float* __restrict__ logit_base, int rows_are_selected,
                                                           const Q* __restrict__ q_logits, float temperature,
                                                           const float* __restrict__ u_sample, SamplerBufs sb,
                                                           const int32_t* __restrict__ n_accepted, int k_max,
                                                           int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_emitted,
                                                           uint32_t* __restrict__ near_tie) {
-  __shared__ double s_scan[256];
+  __shared__ double s_scan[kPickThreads];
   __shared__ int s_i[2];
   const int b = blockIdx.x, tid = threadIdx.x;
   if (sb.sel_mode[b] == MODE_NONE) return;
@@ -580,11 +581,12 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   // slice level inside the chosen chunk
   const int chunk = (V + kSampleChunks - 1) / kSampleChunks;
   const int c0 = min(cs * chunk, V), c1 = min(c0 + chunk, V);
-  const int slice = (c1 - c0 + 255) / 256;
+  const int slice = (c1 - c0 + kPickThreads - 1) / kPickThreads;
   const int j0 = min(c0 + tid * slice, c1), j1 = min(j0 + slice, c1);
   // One workgroup per sequence: nothing hides a load's latency here, so a thread requests its whole slice (up to
-  // kW logits of p and q) at once and keeps the weights in registers for the walk below.
-  constexpr int kW = 24;
+  // kW logits of p and q) at once and keeps the weights in registers for the walk below.  1024 threads: the two
+  // float64 exponentials per token are the bulk of this kernel and only B workgroups share the GPU.
+  constexpr int kW = 8;
   const bool in_regs = slice <= kW;
   double wv[kW];
   double csum = 0.0;
@@ -598,7 +600,8 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
     }
 #pragma unroll
     for (int i = 0; i < kW; ++i) {
-      wv[i] = (j0 + i < j1) ? r.weight_v(j0 + i, zr[i], qr[i], sp, sq, mode) : 0.0;
+      wv[i] = 0.0;
+      if (j0 + i < j1) wv[i] = r.weight_v(j0 + i, zr[i], qr[i], sp, sq, mode);
       csum += wv[i];
     }
   } else {
@@ -606,7 +609,7 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(int V, const float* __
   }
   s_scan[tid] = csum;
   __syncthreads();
-  for (int o = 1; o < 256; o <<= 1) {
+  for (int o = 1; o < kPickThreads; o <<= 1) {
     const double v = (tid >= o) ? s_scan[tid - o] : 0.0;
     __syncthreads();
     s_scan[tid] += v;
@@ -726,7 +729,7 @@ static void launch_sample_t(int B, int k_max, int V, const float* logit_base, bo
   const int sel = rows_are_selected ? 1 : 0;
   hipLaunchKernelGGL((sample_sum_kernel<Q, FILT>), dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
   hipLaunchKernelGGL((sample_mass_kernel<Q, FILT>), dim3(kSampleChunks, B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, sb);
-  hipLaunchKernelGGL((sample_pick_kernel<Q, FILT>), dim3(B), dim3(256), 0, st, V, logit_base, sel, q_logits, temperature, u_sample, sb,
+  hipLaunchKernelGGL((sample_pick_kernel<Q, FILT>), dim3(B), dim3(kPickThreads), 0, st, V, logit_base, sel, q_logits, temperature, u_sample, sb,
                      n_accepted, k_max, out_tokens, n_emitted, near_tie);
 }
 void launch_sample(int B, int k_max, int V, const float* logit_base, bool rows_are_selected, const void* q_logits,
