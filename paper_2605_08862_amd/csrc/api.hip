@@ -380,8 +380,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   int attn_s_min, attn_force;
   attention_plan_params(s, B, k_max, &attn_s_min, &attn_force);
   launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, attn_s_min, attn_force, s.L, st);
-  launch_embed(s, p, M_max, c->embed, c->h, st);
-  launch_rope_angles(s, p, M_max, c->inv_freq, c->rope_cos, c->rope_sin, st);
+  launch_embed(s, p, M_max, c->embed, c->h, c->inv_freq, c->rope_cos, c->rope_sin, st);
   const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
   int pending = 0;                              // slabs of the last residual projection not yet added to h
   for (int l = 0; l < s.L; ++l) {

@@ -117,16 +117,16 @@ void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_sl
                    const int32_t* n_commit, hipStream_t st);
 void launch_clear_status(int32_t* status, hipStream_t st);
 // elementwise.hip
-void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, hipStream_t st);
+// also fills the step's rotary tables cos_t / sin_t [M_max][D/2] (shared by all layers)
+void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, const double* inv_freq,
+                  float* cos_t, float* sin_t, hipStream_t st);
 // h[r] += sum of n_slabs slabs [M_max, d] (n_slabs may be 0), then out[r] = RMSNorm(h[r]).
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
                     const float* gain, void* out, hipStream_t st);
 // qkv is the float32 projection, given as n_slabs >= 1 slabs [M_max, Nqkv] that are summed.
 // inv_freq: [D/2] float64 table written by launch_rope_table.
 void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st);
-// cos_t / sin_t: [M_max][D/2] tables of the step's packed rows (launch_rope_angles, once per step).
-void launch_rope_angles(const Shape& s, const Plan& p, int M_max, const double* inv_freq, float* cos_t, float* sin_t,
-                        hipStream_t st);
+// cos_t / sin_t: [M_max][D/2] tables of the step's packed rows (filled by launch_embed, once per step).
 void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* cos_t, const float* sin_t,
                         const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,

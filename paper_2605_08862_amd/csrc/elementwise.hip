@@ -4,13 +4,34 @@
 // coalesced row access, one workgroup per packed row.
 #include "common.h"
 
+// cos / sin of the rotary angle of packed row r (absolute position c_b + i) and pair j.  The angle is formed in
+// float64 (at positions of 3e4 a float32 angle is already off by ~2e-3 rad), reduced to [-pi, pi] in float64 and
+// only then handed to the float32 sine / cosine.
+__device__ __forceinline__ void rope_angle(const Plan& p, int r, int j, int half, const double* __restrict__ inv_freq,
+                                           float* __restrict__ cos_t, float* __restrict__ sin_t) {
+  const int pos = p.seq_c[p.row_seq[r]] + p.row_pos[r];
+  const double ang = (double)pos * inv_freq[j];
+  const double two_pi_hi = 6.283185307179586, two_pi_lo = 2.4492935982947064e-16;
+  const double n = rint(ang * 0.15915494309189535);
+  const double red = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
+  float sn, cs;
+  sincosf((float)red, &sn, &cs);
+  cos_t[(size_t)r * half + j] = cs;
+  sin_t[(size_t)r * half + j] = sn;
+}
+
+// Token embedding of every packed row and, in the same launch, the row's rotary cos / sin table entries (the table
+// [M_max][D/2] is shared by all layers of the step).
 template <typename T>
-__global__ void __launch_bounds__(256) embed_kernel(Plan p, int d, const T* __restrict__ embed, float* __restrict__ h) {
+__global__ void __launch_bounds__(256) embed_kernel(Plan p, int d, const T* __restrict__ embed, float* __restrict__ h,
+                                                    int D, const double* __restrict__ inv_freq,
+                                                    float* __restrict__ cos_t, float* __restrict__ sin_t) {
   int r = blockIdx.x;
   if (r >= p.n_rows[0]) return;
   const T* src = embed + (size_t)p.row_tok[r] * d;
   float* dst = h + (size_t)r * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = to_f32<T>(src[i]);
+  if ((int)threadIdx.x < D / 2) rope_angle(p, r, threadIdx.x, D / 2, inv_freq, cos_t, sin_t);
 }
 
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
@@ -107,27 +128,8 @@ __global__ void rope_table_kernel(int D, float theta, double* __restrict__ inv_f
   if (j < D / 2) inv_freq[j] = exp2(-2.0 * (double)j / (double)D * log2((double)theta));
 }
 
-// cos / sin of the rotary angles of every packed row (absolute position c_b + i), once per step: the table
-// [M_max][D/2] is shared by all layers.  Angles are formed in float64 (at positions of 3e4 a float32 angle
-// is already off by ~2e-3 rad), reduced to [-pi, pi] in float64 and only then handed to the float32 sine /
-// cosine.
-__global__ void __launch_bounds__(64) rope_angles_kernel(Plan p, int D, const double* __restrict__ inv_freq,
-                                                         float* __restrict__ cos_t, float* __restrict__ sin_t) {
-  const int r = blockIdx.x, j = threadIdx.x, half = D / 2;
-  if (r >= p.n_rows[0] || j >= half) return;
-  const int pos = p.seq_c[p.row_seq[r]] + p.row_pos[r];
-  const double ang = (double)pos * inv_freq[j];
-  const double two_pi_hi = 6.283185307179586, two_pi_lo = 2.4492935982947064e-16;
-  const double n = rint(ang * 0.15915494309189535);
-  const double red = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
-  float sn, cs;
-  sincosf((float)red, &sn, &cs);
-  cos_t[(size_t)r * half + j] = cs;
-  sin_t[(size_t)r * half + j] = sn;
-}
-
 // Rotary (pairs (j, j + D/2), angle = position * theta^(-2j/D)) on q and k of packed row r at
-// absolute position c_b + i, with the cos / sin table of rope_angles_kernel.  The QKV projection arrives in
+// absolute position c_b + i, with the cos / sin table filled by embed_kernel.  The QKV projection arrives in
 // float32, as n_slabs K-split slabs that are summed here (so each of q, k, v is rounded exactly once, after
 // the rotation): q goes to the query buffer (float16 for bf16 models: it is an attention operand, not
 // cache data), k and v to the slot's page in the cache dtype.
@@ -218,9 +220,12 @@ __global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D,
   }
 }
 
-void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, hipStream_t st) {
-  if (s.dtype == BS_F32) hipLaunchKernelGGL(embed_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, (const float*)embed, h);
-  else hipLaunchKernelGGL(embed_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, s.d, (const bf16*)embed, h);
+void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, const double* inv_freq,
+                  float* cos_t, float* sin_t, hipStream_t st) {
+  if (s.dtype == BS_F32)
+    hipLaunchKernelGGL(embed_kernel<float>, dim3(M_max), dim3(256), 0, st, p, s.d, (const float*)embed, h, s.D, inv_freq, cos_t, sin_t);
+  else
+    hipLaunchKernelGGL(embed_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, s.d, (const bf16*)embed, h, s.D, inv_freq, cos_t, sin_t);
 }
 void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
                     const float* gain, void* out, hipStream_t st) {
@@ -232,10 +237,6 @@ void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const fl
 }
 void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st) {
   hipLaunchKernelGGL(rope_table_kernel, dim3(1), dim3(64), 0, st, s.D, s.theta, inv_freq);
-}
-void launch_rope_angles(const Shape& s, const Plan& p, int M_max, const double* inv_freq, float* cos_t, float* sin_t,
-                        hipStream_t st) {
-  hipLaunchKernelGGL(rope_angles_kernel, dim3(M_max), dim3(64), 0, st, p, s.D, inv_freq, cos_t, sin_t);
 }
 void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* cos_t, const float* sin_t,
                         const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
