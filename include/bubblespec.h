@@ -17,8 +17,9 @@
  *   - `stream` is a hipStream_t passed as void*.  Step calls only enqueue work on it and never
  *     synchronise with the host.  Conditions only the device can see (a sequence running past
  *     its pages, a token id outside the vocabulary, a draft length above k_max) set bits in a
- *     device status word; the affected sequence is skipped, nothing is written out of bounds,
- *     and bs_poll_status() (the one synchronising call) returns the word.
+ *     device status word; the affected sequence is skipped (no row of it is embedded, appended,
+ *     judged or committed: n_accepted = n_emitted = 0, out_tokens = -1, ctx_len unchanged), nothing
+ *     is written out of bounds, and bs_poll_status() (the one synchronising call) returns the word.
  *   - Row packing: sequence b contributes k_b+1 query rows; rows are packed in batch order,
  *     row0_b = sum_{b'<b}(k_b'+1), M = sum_b (k_b+1).  Draft rows (for q_logits) are packed the
  *     same way with k_b rows per sequence, T_d = sum_b k_b.  The packing is computed on the
@@ -51,7 +52,9 @@ enum {
   BS_FAULT_KV_PAGES = 2,  /* c_b + k_b + 1 exceeds the pages of the slot / bad page id */
   BS_FAULT_TOKEN_ID = 4,  /* a token id outside [0, vocab)                         */
   BS_FAULT_COMMIT = 8,    /* n_commit[b] outside [0, k_b + 1]                      */
-  BS_FAULT_SLOT = 16      /* seq_slot[b] outside [0, n_slots) or used twice        */
+  BS_FAULT_SLOT = 16,     /* seq_slot[b] outside [0, n_slots) or used twice        */
+  BS_FAULT_RANGE = 32     /* bf16 models: a value left the float16 range (see bs_model_desc.dtype) and was
+                             saturated; the step's results are finite but no longer those of the model */
 };
 
 #define BS_PAGE_TOKENS 64 /* tokens per KV page (fixed) */
@@ -62,7 +65,12 @@ enum {
  * with an untied LM head and no biases. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-  int32_t dtype;   /* bs_dtype of weights, KV cache and inter-kernel activations */
+  int32_t dtype;   /* bs_dtype of the weights and of the KV cache (data at rest).  BS_BF16 models compute with
+                      float16 matrix operands and float32 accumulation: weights and cached K/V are bf16 VALUES
+                      held in float16 encoding (exact for 6.1e-5 <= |x| <= 65504, smaller magnitudes lose low
+                      bits), activations between operators are float16, the residual stream is float32.  Any
+                      weight, K/V element or activation with |x| > 65504 (or NaN) is saturated to +-65504 (NaN
+                      to 0) and reported through BS_FAULT_RANGE; nothing infinite enters a matrix product. */
   float rms_eps;   /* RMSNorm epsilon */
   float rope_theta;
 } bs_model_desc;
@@ -219,6 +227,13 @@ bs_status bs_set_filter(bs_ctx* ctx, int top_k, float top_p, float* logits_scrat
  * BS_EINVAL; a value outside [0,k_b+1] sets BS_FAULT_COMMIT and leaves that slot unchanged. */
 bs_status bs_kv_commit(bs_ctx* ctx, int B, const int32_t* seq_slot, const int32_t* n_commit,
                        void* stream);
+
+/* Alg. 1 keeps the rollout y per sequence; its length on the cache side is the committed length c of the slot.
+ * Copies ctx_len[seq_slot[b]] to ctx_len_out[b] for b < B (both dev), in stream order with the commits before
+ * it.  (ctx_len itself is the caller's buffer and may also be read directly; this call gives the lengths of a
+ * batch in batch order without the caller indexing by slot.)  A slot outside [0, n_slots) yields -1 and sets
+ * BS_FAULT_SLOT.  Errors: BS_EINVAL (null), BS_ESHAPE (B < 1). */
+bs_status bs_kv_lengths(bs_ctx* ctx, int B, const int32_t* seq_slot /*[B]*/, int32_t* ctx_len_out /*[B]*/, void* stream);
 
 /* Cache import / export: copies n dense rows [n, Hkv, D] (dtype = desc.dtype, dev) of one layer
  * to / from positions pos0 .. pos0+n of a slot, through the block table.  Does not touch ctx_len.

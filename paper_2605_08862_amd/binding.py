@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(_HERE, "libbubblespec.so")
 
 BS_OK, BS_EINVAL, BS_ESHAPE, BS_ECAPACITY, BS_ESTATE, BS_EHIP = range(6)
 BS_F32, BS_BF16 = 0, 1
-BS_FAULT_DRAFT_LEN, BS_FAULT_KV_PAGES, BS_FAULT_TOKEN_ID, BS_FAULT_COMMIT, BS_FAULT_SLOT = 1, 2, 4, 8, 16
+BS_FAULT_DRAFT_LEN, BS_FAULT_KV_PAGES, BS_FAULT_TOKEN_ID, BS_FAULT_COMMIT, BS_FAULT_SLOT, BS_FAULT_RANGE = 1, 2, 4, 8, 16, 32
 BS_PAGE_TOKENS = 64
 BS_MAX_K = 30
 STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", "BS_EHIP"]
@@ -19,7 +19,7 @@ STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", 
 EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs_pool_bind", "bs_draft_lookup",
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
            "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end", "bs_index_build", "bs_index_free",
-           "bs_index_bind", "bs_set_filter"]
+           "bs_index_bind", "bs_set_filter", "bs_kv_lengths"]
 PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
                 "sample": 7, "lookup": 8, "empty": 9}
 
@@ -75,6 +75,7 @@ def lib():
                                                 vp, vp, vp, vp]
         L.bs_set_filter.argtypes = [vp, i32, f32, vp]
         L.bs_kv_commit.argtypes = [vp, i32, vp, vp, vp]
+        L.bs_kv_lengths.argtypes = [vp, i32, vp, vp, vp]
         L.bs_kv_write.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.bs_kv_read.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.bs_poll_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
@@ -214,6 +215,10 @@ def bs_set_filter(ctx, top_k, top_p, logits_scratch):
 
 def bs_kv_commit(ctx, B, seq_slot, n_commit):
     _check(ctx, lib().bs_kv_commit(ctx, B, _ptr(seq_slot), _ptr(n_commit), _stream()))
+
+
+def bs_kv_lengths(ctx, B, seq_slot, ctx_len_out):
+    _check(ctx, lib().bs_kv_lengths(ctx, B, _ptr(seq_slot), _ptr(ctx_len_out), _stream()))
 
 
 def bs_kv_write(ctx, layer, slot, pos0, n, k_rows, v_rows):

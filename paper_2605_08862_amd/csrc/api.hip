@@ -84,12 +84,8 @@ bs_status check_desc(const bs_model_desc* d, int B_max, int k_max) {
   return BS_OK;
 }
 
-// Lays the workspace out; with base == nullptr only measures it.
-size_t carve(bs_ctx* c, char* base) {
-  Carver w{base};
-  const Shape& s = c->s;
-  const int B = c->B_max, M = c->M_max;
-  Plan& p = c->plan;
+// Plan arrays of B sequences / M packed rows; with_attention also lays out the attention work list.
+void carve_plan(Carver& w, Plan& p, int B, int M, bool with_attention, int n_layers) {
   p.status = w.take<int32_t>(64);
   p.n_rows = w.take<int32_t>(64);
   p.row_start = w.take<int32_t>(B + 1);
@@ -101,30 +97,23 @@ size_t carve(bs_ctx* c, char* base) {
   p.row_pos = w.take<int32_t>(M);
   p.row_tok = w.take<int32_t>(M);
   p.row_target = w.take<int32_t>(M);
+  if (!with_attention) {
+    p.attn_meta = p.item_start = p.item_seq = p.item_chunk = p.attn_queue = nullptr;
+    return;
+  }
   p.attn_meta = w.take<int32_t>(64);
   p.item_start = w.take<int32_t>(B + 1);
   p.item_seq = w.take<int32_t>(attn_item_capacity(B, kAttnMaxSmin));
   p.item_chunk = w.take<int32_t>(attn_item_capacity(B, kAttnMaxSmin));
-  p.attn_queue = w.take<int32_t>((size_t)8 * s.L);
-  c->h = w.take<float>((size_t)M * s.d);
-  c->inv_freq = w.take<double>(64);
-  c->rope_cos = w.take<float>((size_t)M * 64);
-  c->rope_sin = w.take<float>((size_t)M * 64);
-  c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
-  c->qkv = w.take<float>((size_t)M * s.Nqkv());
-  c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
-  c->slabs = (s.dtype == BS_BF16)
-                 ? w.take<float>((size_t)kMaxGemmSplit * M * (s.Nqkv() > s.d ? s.Nqkv() : s.d))
-                 : nullptr;
-  c->attn_out = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
-  c->act = w.take<char>((size_t)M * s.F * elt(s.dtype));
-  c->hf = w.take<char>((size_t)M * s.d * elt(s.dtype));
-  c->attn_scratch = w.take<char>(attention_scratch_bytes(s, B, c->k_max));
-  c->n_vtiles = lmhead_vtiles(s.V);
-  SamplerBufs& sb = c->sb;
-  sb.part_max = w.take<float>((size_t)c->n_vtiles * M);
-  sb.part_sum = w.take<float>((size_t)c->n_vtiles * M);
-  sb.part_arg = w.take<int32_t>((size_t)c->n_vtiles * M);
+  p.attn_queue = w.take<int32_t>((size_t)8 * n_layers);
+}
+
+// Sampler buffers of B sequences / M packed rows with n_vtiles statistics tiles per row (sel_logits and the
+// filter thresholds are laid out by the caller that needs them).
+void carve_sampler(Carver& w, SamplerBufs& sb, int B, int M, int n_vtiles) {
+  sb.part_max = w.take<float>((size_t)n_vtiles * M);
+  sb.part_sum = w.take<float>((size_t)n_vtiles * M);
+  sb.part_arg = w.take<int32_t>((size_t)n_vtiles * M);
   sb.fold_max = w.take<float>((size_t)16 * M);
   sb.fold_sum = w.take<float>((size_t)16 * M);
   sb.fold_arg = w.take<int32_t>((size_t)16 * M);
@@ -146,6 +135,32 @@ size_t carve(bs_ctx* c, char* base) {
   sb.f_key = w.take<uint32_t>(M);
   sb.f_idx = w.take<int32_t>(M);
   sb.f_lse = w.take<float>(M);
+  sb.sel_logits = nullptr;
+}
+
+// Lays the workspace out; with base == nullptr only measures it.
+size_t carve(bs_ctx* c, char* base) {
+  Carver w{base};
+  const Shape& s = c->s;
+  const int B = c->B_max, M = c->M_max;
+  carve_plan(w, c->plan, B, M, true, s.L);
+  c->h = w.take<float>((size_t)M * s.d);
+  c->inv_freq = w.take<double>(64);
+  c->rope_cos = w.take<float>((size_t)M * 64);
+  c->rope_sin = w.take<float>((size_t)M * 64);
+  c->a = w.take<char>((size_t)M * s.d * elt(s.dtype));          // float16 and bf16 have the same size
+  c->qkv = w.take<float>((size_t)M * s.Nqkv());
+  c->q = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
+  c->slabs = (s.dtype == BS_BF16)
+                 ? w.take<float>((size_t)kMaxGemmSplit * M * (s.Nqkv() > s.d ? s.Nqkv() : s.d))
+                 : nullptr;
+  c->attn_out = w.take<char>((size_t)M * s.Hq * s.D * elt(s.dtype));
+  c->act = w.take<char>((size_t)M * s.F * elt(s.dtype));
+  c->hf = w.take<char>((size_t)M * s.d * elt(s.dtype));
+  c->attn_scratch = w.take<char>(attention_scratch_bytes(s, B, c->k_max));
+  c->n_vtiles = lmhead_vtiles(s.V);
+  SamplerBufs& sb = c->sb;
+  carve_sampler(w, sb, B, M, c->n_vtiles);
   if (s.dtype == BS_F32) {
     c->full_logits = w.take<float>((size_t)M * s.V);
     sb.sel_logits = nullptr;
@@ -247,6 +262,7 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   if (carve(c, nullptr) > workspace_bytes) { delete c; return BS_ECAPACITY; }
   carve(c, (char*)workspace);
   const int L = desc->n_layers;
+  launch_clear_status(c->plan.status, (hipStream_t)stream);   // before the packing kernels, which may set BS_FAULT_RANGE
   for (int l = 0; l < L; ++l) {
     if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->mlp_norm[l] || !w->w_gate_up[l] || !w->w_down[l] ||
         !kv->k_pages[l] || !kv->v_pages[l]) { delete c; return BS_EINVAL; }
@@ -260,10 +276,10 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
     } else {       // one-time re-pack into MFMA operand order (float16); the originals are not used afterwards
       const Shape& s = c->s;
       hipStream_t ps = (hipStream_t)stream;
-      launch_pack_weight(w->wqkv[l], s.Nqkv(), s.d, c->pk_qkv[l], ps);
-      launch_pack_weight(w->wo[l], s.d, s.Hq * s.D, c->pk_o[l], ps);
-      launch_pack_weight(w->w_gate_up[l], 2 * s.F, s.d, c->pk_gu[l], ps);
-      launch_pack_weight(w->w_down[l], s.d, s.F, c->pk_down[l], ps);
+      launch_pack_weight(w->wqkv[l], s.Nqkv(), s.d, c->pk_qkv[l], c->plan.status, ps);
+      launch_pack_weight(w->wo[l], s.d, s.Hq * s.D, c->pk_o[l], c->plan.status, ps);
+      launch_pack_weight(w->w_gate_up[l], 2 * s.F, s.d, c->pk_gu[l], c->plan.status, ps);
+      launch_pack_weight(w->w_down[l], s.d, s.F, c->pk_down[l], c->plan.status, ps);
       c->wqkv.push_back(c->pk_qkv[l]);
       c->wo.push_back(c->pk_o[l]);
       c->w_gate_up.push_back(c->pk_gu[l]);
@@ -275,14 +291,13 @@ bs_status bs_create(const bs_model_desc* desc, const bs_weights* w, const bs_kv_
   c->embed = w->embed;
   c->lm_head = w->lm_head;
   if (desc->dtype == BS_BF16) {
-    launch_pack_weight(w->lm_head, desc->vocab, desc->d_model, c->pk_lm, (hipStream_t)stream);
+    launch_pack_weight(w->lm_head, desc->vocab, desc->d_model, c->pk_lm, c->plan.status, (hipStream_t)stream);
     c->lm_head = c->pk_lm;
   }
   c->final_norm = w->final_norm;
   c->kv = KvView{kv->n_pages, kv->n_slots, kv->max_pages_per_seq, kv->block_table, kv->ctx_len};
   launch_rope_table(c->s, c->inv_freq, (hipStream_t)stream);
   launch_attention_init(c->s, c->B_max, c->attn_scratch, (hipStream_t)stream);
-  launch_clear_status(c->plan.status, (hipStream_t)stream);
   st = check_hip(c);
   if (st != BS_OK) { bs_destroy(c); return st; }
   *out = c;
@@ -393,7 +408,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
       int nq;
       { ProfScope ps(c, BS_PROF_GEMM_QKV, st);
         nq = launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.Nqkv(), s.d, c->a, nullptr, c->wqkv[l],
-                         slab_mode ? (void*)c->slabs : (void*)c->qkv, st); }
+                         slab_mode ? (void*)c->slabs : (void*)c->qkv, p.status, st); }
       launch_rope_append(s, p, c->kv, M_max, c->rope_cos, c->rope_sin, slab_mode ? c->slabs : c->qkv, nq > 0 ? nq : 1, c->q,
                          c->k_pages[l], c->v_pages[l], st);
     }
@@ -401,17 +416,17 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
     { ProfScope ps(c, BS_PROF_GEMM_O, st);
       pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l],
-                            slab_mode ? (void*)c->slabs : (void*)c->h, st); }
+                            slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->mlp_norm[l], c->a, st);
     { ProfScope ps(c, BS_PROF_GEMM_GATE_UP, st);
-      launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, st); }
+      launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, p.status, st); }
     { ProfScope ps(c, BS_PROF_GEMM_DOWN, st);
       pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l],
-                            slab_mode ? (void*)c->slabs : (void*)c->h, st); }
+                            slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
   }
   launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->final_norm, c->hf, st);
   if (logits_debug && s.dtype == BS_F32)
-    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, logits_debug, st);
+    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, logits_debug, p.status, st);
   if (logits_debug && s.dtype == BS_BF16) {
     // same kernel and loop order as the fused path of bs_accept_resample, so the values are identical
     launch_lmhead_stats(s, p, M_max, c->hf, c->lm_head, 1.0f, c->sb, logits_debug, st);
@@ -446,7 +461,7 @@ static bs_status accept_common(bs_ctx* c, int B, int V, const float* given_logit
     n_vtiles = (V + 1023) / 1024;
     sample_base = given_logits;
   } else if (s.dtype == BS_F32) {
-    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, c->full_logits, st);
+    launch_gemm(s.dtype, EPI_STORE_F32, p.n_rows, M_max, s.V, s.d, c->hf, nullptr, c->lm_head, c->full_logits, p.status, st);
     launch_logit_stats(p, M_max, V, c->full_logits, inv_temp, c->sb, st);
     n_vtiles = (V + 1023) / 1024;
     sample_base = c->full_logits;
@@ -540,6 +555,14 @@ bs_status bs_kv_commit(bs_ctx* c, int B, const int32_t* seq_slot, const int32_t*
   return check_hip(c);
 }
 
+bs_status bs_kv_lengths(bs_ctx* c, int B, const int32_t* seq_slot, int32_t* ctx_len_out, void* stream) {
+  if (!c) return BS_EINVAL;
+  if (!seq_slot || !ctx_len_out) return fail(c, BS_EINVAL, "bs_kv_lengths: null pointer");
+  if (B < 1) return fail(c, BS_ESHAPE, "bs_kv_lengths: B must be positive");
+  launch_kv_lengths(c->kv, B, seq_slot, ctx_len_out, c->plan.status, (hipStream_t)stream);
+  return check_hip(c);
+}
+
 static bs_status kv_copy(bs_ctx* c, int layer, int slot, int pos0, int n, void* k_rows, void* v_rows, bool to_pages,
                          void* stream) {
   if (!c) return BS_EINVAL;
@@ -548,7 +571,7 @@ static bs_status kv_copy(bs_ctx* c, int layer, int slot, int pos0, int n, void* 
     return fail(c, BS_ESHAPE, "bs_kv_write/read: layer, slot or range out of bounds");
   if ((long)pos0 + n > (long)c->kv.max_pages * kPage) return fail(c, BS_ECAPACITY, "bs_kv_write/read: beyond the slot's pages");
   launch_kv_copy(c->s, c->kv, slot, pos0, n, c->k_pages[layer], c->v_pages[layer], k_rows, v_rows, to_pages,
-                 (hipStream_t)stream);
+                 c->plan.status, (hipStream_t)stream);
   return check_hip(c);
 }
 

@@ -29,7 +29,6 @@
 // float32 models use the plain kernel in attn_simple.h.
 #include "attn_simple.h"
 #include "gemm_mfma.h"
-#include <stdlib.h>
 #include <type_traits>
 
 namespace {
@@ -66,7 +65,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const int32_t* __restric
                                                         const f16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
                                                         int32_t* __restrict__ counters, int32_t* __restrict__ queue,
-                                                        int q_blocks) {
+                                                        int q_blocks, int32_t* __restrict__ status) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product
   constexpr int DT = D / 32;            // 32-wide d tiles of the output
   constexpr int RP = 32 * NQ * QG;      // padded query rows per workgroup
@@ -332,11 +331,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const int32_t* __restric
           for (int e = 0; e < 4; ++e) acc[e] += v[e] * mw[w];
         }
         if (n_ch == 1) {
-          typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-          f16x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (f16)(acc[e] * inv);
-          *(f16x4*)(dst + ch * 4) = v;
+          *(f16x4*)(dst + ch * 4) = to_f16x4_guarded(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv, status);
         } else {
           *(f32x4*)(part_o + pr * D + ch * 4) = acc;
         }
@@ -387,13 +382,9 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const int32_t* __restric
     const float inv = 1.0f / lt;
     f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
 #pragma unroll
-    for (int j = 0; j < CH / TPR; ++j) {
-      typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-      f16x4 v;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = (f16)(acc[j][e] * inv);
-      *(f16x4*)(dst + (sub + j * TPR) * 4) = v;
-    }
+    for (int j = 0; j < CH / TPR; ++j)
+      *(f16x4*)(dst + (sub + j * TPR) * 4) =
+          to_f16x4_guarded(acc[j][0] * inv, acc[j][1] * inv, acc[j][2] * inv, acc[j][3] * inv, status);
   };
   auto flush = [&]() {
     __syncthreads();
@@ -469,8 +460,6 @@ extern "C" void bs_debug_attention_shape(int q_blocks, int n_chunks) {
 // the token chunks of the work list, which the plan kernel sizes on the device from s_min = wanted (sequence,
 // chunk) items.
 static void launch_shape(const Shape& s, int B, int k_max, int& q_blocks, int& s_min, int& force_chunks) {
-  static const char* split_env = getenv("BS_ATTN_SPLIT");          // tuning aids
-  static const char* qb_env = getenv("BS_ATTN_QBLOCKS");
   const int tiles = rows_padded(s, k_max) / 32;                    // 1, 2 or 4
   const int units = B * s.Hkv;
   q_blocks = 1;
@@ -480,11 +469,11 @@ static void launch_shape(const Shape& s, int B, int k_max, int& q_blocks, int& s
   // stream every K/V tile through L2 four times (measured, 7B heads: 4 sequences of 60k tokens 137 us with two
   // blocks against 196 us with four; ragged batch of 128: 627 us against 729 us).
   if (tiles == 4) q_blocks = 2;
-  const int qb_forced = g_force_q_blocks ? g_force_q_blocks : (qb_env ? atoi(qb_env) : 0);
+  const int qb_forced = g_force_q_blocks;
   if (qb_forced >= 1 && qb_forced <= tiles && tiles % qb_forced == 0) q_blocks = qb_forced;
   s_min = (256 + s.Hkv * q_blocks - 1) / (s.Hkv * q_blocks);
   if (s_min > kAttnMaxSmin) s_min = kAttnMaxSmin;
-  force_chunks = g_force_n_chunks ? g_force_n_chunks : (split_env ? atoi(split_env) : 0);
+  force_chunks = g_force_n_chunks;
 }
 
 void attention_plan_params(const Shape& s, int B, int k_max, int* s_min, int* force_chunks) {
@@ -528,7 +517,8 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p.seq_k, p.seq_c, p.row_start, p.seq_slot, p.attn_meta,
                      p.item_start, p.item_seq, p.item_chunk, kv.block_table, kv.max_pages, kv.n_pages, n_units, s.Hq,
                      s.Hkv, scale_log2e, (const f16*)q,
-                     (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, counters, p.attn_queue + 8 * layer, q_blocks);
+                     (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o, part_ml, counters, p.attn_queue + 8 * layer, q_blocks,
+                     p.status);
   if (prof_token) attention_prof_mark(prof_token, st, false);
 }
 
@@ -536,15 +526,9 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int layer
                       const void* q, const void* k_pages, const void* v_pages, void* out, void* scratch,
                       void* prof_token, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)s.D);
-  static const bool force_simple = getenv("BS_SIMPLE_ATTN") != nullptr;   // debugging aid
   if (s.dtype == BS_F32) {
     hipLaunchKernelGGL((attn_simple_kernel<float, float>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
                        (const float*)q, (const float*)k_pages, (const float*)v_pages, (float*)out);
-    return;
-  }
-  if (force_simple) {
-    hipLaunchKernelGGL((attn_simple_kernel<f16, f16>), dim3(M_max, s.Hq), dim3(256), 0, st, p, kv, s.Hq, s.Hkv, s.D, scale,
-                       (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out);
     return;
   }
   int q_blocks, s_min, force_chunks;

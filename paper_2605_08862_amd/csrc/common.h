@@ -17,6 +17,33 @@ template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // RNE
 
+// ---------------------------------------------------------------------------------------------
+// float16 range guard.  bf16 models keep every matrix operand that is produced during the step
+// (normalised rows, rotated queries, appended K/V, attention output, gated MLP activation) in IEEE
+// float16, whose largest finite value is 65504.  A producer converts four values at a time and
+// tests the packed result: a float16 is infinite or NaN iff its exponent field is all ones, i.e.
+// iff (bits & 0x7fff) + 0x0400 carries into bit 15.  When that happens (never for sane models) the
+// values are saturated to +-65504 (NaN becomes 0) and BS_FAULT_RANGE is set in the status word, so
+// that no infinity or NaN enters a matrix product silently.
+// ---------------------------------------------------------------------------------------------
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bool f16x4_out_of_range(f16x4 v) {
+  const u32x2 u = __builtin_bit_cast(u32x2, v);
+  return ((((u[0] & 0x7fff7fffu) + 0x04000400u) | ((u[1] & 0x7fff7fffu) + 0x04000400u)) & 0x80008000u) != 0u;
+}
+__device__ __forceinline__ float f16_saturate(float x) { return x != x ? 0.f : fminf(fmaxf(x, -65504.f), 65504.f); }
+// (a, b, c, d) -> four float16 values, saturated and flagged if any leaves the float16 range
+__device__ __forceinline__ f16x4 to_f16x4_guarded(float a, float b, float c, float d, int32_t* __restrict__ status) {
+  f16x4 v = f16x4{(f16)a, (f16)b, (f16)c, (f16)d};
+  if (f16x4_out_of_range(v)) {
+    v = f16x4{(f16)f16_saturate(a), (f16)f16_saturate(b), (f16)f16_saturate(c), (f16)f16_saturate(d)};
+    atomicOr(status, BS_FAULT_RANGE);
+  }
+  return v;
+}
+
 constexpr int kPage = BS_PAGE_TOKENS;   // tokens per KV page
 constexpr int kTile = 32;               // tokens per MFMA tile inside a page (bf16 layout)
 
@@ -116,6 +143,7 @@ void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, c
 void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot,
                    const int32_t* n_commit, hipStream_t st);
 void launch_clear_status(int32_t* status, hipStream_t st);
+void launch_kv_lengths(const KvView& kv, int B, const int32_t* seq_slot, int32_t* out, int32_t* status, hipStream_t st);
 // elementwise.hip
 // also fills the step's rotary tables cos_t / sin_t [M_max][D/2] (shared by all layers)
 void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, const double* inv_freq,
@@ -130,7 +158,7 @@ void launch_rope_table(const Shape& s, double* inv_freq, hipStream_t st);
 void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_max, const float* cos_t, const float* sin_t,
                         const float* qkv, int n_slabs, void* q_out, void* k_pages, void* v_pages, hipStream_t st);
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
-                    void* k_rows, void* v_rows, bool to_pages, hipStream_t st);
+                    void* k_rows, void* v_rows, bool to_pages, int32_t* status, hipStream_t st);
 // qkv_rope.hip   QKV projection + rotary + KV append in one kernel (bf16 models with head size 128); A = normed
 // rows (float16), Wp = packed wqkv.
 bool qkv_rope_supported(const Shape& s);
@@ -143,11 +171,12 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_
 // slab buffer [split][M_max][N] and the consumer sums the slabs), or 0 when `out` was updated in place
 // (float32 models).
 constexpr int kMaxGemmSplit = 8;
+// status: the step's device status word (float16-range faults of the float16 epilogues).
 int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
                 const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
-                hipStream_t st);
+                int32_t* status, hipStream_t st);
 size_t packed_weight_elems(int N, int K);
-void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st);
+void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, int32_t* status, hipStream_t st);
 // attention.hip
 // attention_plan_params gives the work-list parameters launch_plan needs for the same (B, k_max);
 // launch_attention_init clears the completion counters once, at context creation.

@@ -3,6 +3,7 @@
 // Each moves O(M*d) bytes per layer (<1 % of a step's traffic); they are written for clarity and
 // coalesced row access, one workgroup per packed row.
 #include "common.h"
+#include <type_traits>
 
 // cos / sin of the rotary angle of packed row r (absolute position c_b + i) and pair j.  The angle is formed in
 // float64 (at positions of 3e4 a float32 angle is already off by ~2e-3 rad), reduced to [-pi, pi] in float64 and
@@ -114,10 +115,15 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, 
   for (int it = 0; it < NV; ++it) {
     const int i = (it * 256 + threadIdx.x) * 4;
     if (i < d) {
-      typename Vec4<T>::type w;
+      if constexpr (std::is_same<T, f16>::value) {
+        *(f16x4*)(o + i) = to_f16x4_guarded(v[it][0] * inv * gn[it][0], v[it][1] * inv * gn[it][1],
+                                            v[it][2] * inv * gn[it][2], v[it][3] * inv * gn[it][3], p.status);
+      } else {
+        typename Vec4<T>::type w;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) w[e] = from_f32<T>(v[it][e] * inv * gn[it][e]);
-      *(typename Vec4<T>::type*)(o + i) = w;
+        for (int e = 0; e < 4; ++e) w[e] = from_f32<T>(v[it][e] * inv * gn[it][e]);
+        *(typename Vec4<T>::type*)(o + i) = w;
+      }
     }
   }
 }
@@ -167,10 +173,15 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
         y2[e] = x2[e] * c[e] + x1[e] * sn[e];
       }
       if (hh < Hq) {
+        if constexpr (std::is_same<TQ, f16>::value) {
+          *(f16x4*)(qrow + hh * D + j) = to_f16x4_guarded(y1[0], y1[1], y1[2], y1[3], p.status);
+          *(f16x4*)(qrow + hh * D + j + half) = to_f16x4_guarded(y2[0], y2[1], y2[2], y2[3], p.status);
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          qrow[hh * D + j + e] = from_f32<TQ>(y1[e]);
-          qrow[hh * D + j + half + e] = from_f32<TQ>(y2[e]);
+          for (int e = 0; e < 4; ++e) {
+            qrow[hh * D + j + e] = from_f32<TQ>(y1[e]);
+            qrow[hh * D + j + half + e] = from_f32<TQ>(y2[e]);
+          }
         }
       } else {
         const int kh = hh - Hq;
@@ -178,10 +189,16 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
         // both page layouts)
         TP* k1 = k_pages + pbase + k_index<TP>(D, kh, tok, j);
         TP* k2 = k_pages + pbase + k_index<TP>(D, kh, tok, j + half);
+        if constexpr (std::is_same<TP, f16>::value) {
+          auto rt = [](float x) { return to_f32<T>(from_f32<T>(x)); };
+          *(f16x4*)k1 = to_f16x4_guarded(rt(y1[0]), rt(y1[1]), rt(y1[2]), rt(y1[3]), p.status);
+          *(f16x4*)k2 = to_f16x4_guarded(rt(y2[0]), rt(y2[1]), rt(y2[2]), rt(y2[3]), p.status);
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          k1[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y1[e])));
-          k2[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y2[e])));
+          for (int e = 0; e < 4; ++e) {
+            k1[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y1[e])));
+            k2[e] = from_f32<TP>(to_f32<T>(from_f32<T>(y2[e])));
+          }
         }
       }
     } else {
@@ -190,9 +207,16 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
       const float* x = row + (size_t)(Hq + Hkv) * D + e0;
       f4 v = f4{0.f, 0.f, 0.f, 0.f};
       for (int sl = 0; sl < n_slabs; ++sl) v += *(const f4*)(x + sl * slab_stride);
+      if constexpr (std::is_same<TP, f16>::value) {
+        auto rt = [](float x) { return to_f32<T>(from_f32<T>(x)); };
+        const f16x4 w = to_f16x4_guarded(rt(v[0]), rt(v[1]), rt(v[2]), rt(v[3]), p.status);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        v_pages[pbase + v_index<TP>(D, kh, tok, dd + e)] = from_f32<TP>(to_f32<T>(from_f32<T>(v[e])));
+        for (int e = 0; e < 4; ++e) v_pages[pbase + v_index<TP>(D, kh, tok, dd + e)] = w[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          v_pages[pbase + v_index<TP>(D, kh, tok, dd + e)] = from_f32<TP>(to_f32<T>(from_f32<T>(v[e])));
+      }
     }
   }
 }
@@ -200,7 +224,7 @@ __global__ void __launch_bounds__(256) rope_append_kernel(Plan p, KvView kv, int
 template <typename T, typename TP>
 __global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D, int slot, int pos0, TP* __restrict__ k_pages,
                                                       TP* __restrict__ v_pages, T* __restrict__ k_rows,
-                                                      T* __restrict__ v_rows, int to_pages) {
+                                                      T* __restrict__ v_rows, int to_pages, int32_t* __restrict__ status) {
   int i = blockIdx.x, pos = pos0 + i;
   int page = kv.block_table[(size_t)slot * kv.max_pages + pos / kPage];
   if (page < 0 || page >= kv.n_pages) return;
@@ -211,8 +235,15 @@ __global__ void __launch_bounds__(256) kv_copy_kernel(KvView kv, int Hkv, int D,
     size_t ki = pbase + k_index<TP>(D, kh, tok, dd), vi = pbase + v_index<TP>(D, kh, tok, dd);
     size_t ri = (size_t)i * Hkv * D + idx;
     if (to_pages) {
-      k_pages[ki] = from_f32<TP>(to_f32<T>(k_rows[ri]));
-      v_pages[vi] = from_f32<TP>(to_f32<T>(v_rows[ri]));
+      float kx = to_f32<T>(k_rows[ri]), vx = to_f32<T>(v_rows[ri]);
+      if constexpr (std::is_same<TP, f16>::value) {      // imported bf16 values beyond the float16 range
+        if (!(fabsf(kx) <= 65504.f) || !(fabsf(vx) <= 65504.f)) {
+          kx = f16_saturate(kx); vx = f16_saturate(vx);
+          atomicOr(status, BS_FAULT_RANGE);
+        }
+      }
+      k_pages[ki] = from_f32<TP>(kx);
+      v_pages[vi] = from_f32<TP>(vx);
     } else {
       k_rows[ri] = from_f32<T>(to_f32<TP>(k_pages[ki]));
       v_rows[ri] = from_f32<T>(to_f32<TP>(v_pages[vi]));
@@ -249,12 +280,12 @@ void launch_rope_append(const Shape& s, const Plan& p, const KvView& kv, int M_m
                        qkv, n_slabs, stride, (f16*)q_out, (f16*)k_pages, (f16*)v_pages);
 }
 void launch_kv_copy(const Shape& s, const KvView& kv, int slot, int pos0, int n, void* k_pages, void* v_pages,
-                    void* k_rows, void* v_rows, bool to_pages, hipStream_t st) {
+                    void* k_rows, void* v_rows, bool to_pages, int32_t* status, hipStream_t st) {
   if (n <= 0) return;
   if (s.dtype == BS_F32)
     hipLaunchKernelGGL((kv_copy_kernel<float, float>), dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (float*)k_pages,
-                       (float*)v_pages, (float*)k_rows, (float*)v_rows, to_pages ? 1 : 0);
+                       (float*)v_pages, (float*)k_rows, (float*)v_rows, to_pages ? 1 : 0, status);
   else
     hipLaunchKernelGGL((kv_copy_kernel<bf16, f16>), dim3(n), dim3(256), 0, st, kv, s.Hkv, s.D, slot, pos0, (f16*)k_pages,
-                       (f16*)v_pages, (bf16*)k_rows, (bf16*)v_rows, to_pages ? 1 : 0);
+                       (f16*)v_pages, (bf16*)k_rows, (bf16*)v_rows, to_pages ? 1 : 0, status);
 }

@@ -3,7 +3,6 @@
 // bf16 models run on the f16 MFMA main loop of gemm_mfma.h over packed weights; float32 models (the
 // tiny parity configuration, launch-latency bound) run on a plain LDS-tiled FMA kernel.
 #include "gemm_mfma.h"
-#include <stdlib.h>
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 // same function with the hardware reciprocal (1 ulp): used in the MFMA epilogue, where a full-precision
@@ -78,7 +77,7 @@ __global__ void __launch_bounds__(256) gemm_simple_kernel(const int32_t* __restr
 // ------------------------------------------------------------------ weight packing (once per context)
 // bf16 row-major [N, K] -> float16 MFMA operand order (see gemm_mfma.h); rows beyond N are zero.
 __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16* __restrict__ w, int N, int K, f16* __restrict__ packed,
-                                                          size_t n_chunks) {
+                                                          size_t n_chunks, int32_t* __restrict__ status) {
   const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;     // one 16-byte chunk of the packed array
   if (c >= n_chunks) return;
   const int nk = K / kBK;
@@ -89,8 +88,10 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16* __restrict
   f16x8 v;
   if (n < N) {
     const bf16x8 src = *(const bf16x8*)(w + (size_t)n * K + k);
+    const f16x4 lo = to_f16x4_guarded((float)src[0], (float)src[1], (float)src[2], (float)src[3], status);
+    const f16x4 hi = to_f16x4_guarded((float)src[4], (float)src[5], (float)src[6], (float)src[7], status);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = (f16)(float)src[j];
+    for (int j = 0; j < 4; ++j) { v[j] = lo[j]; v[4 + j] = hi[j]; }
   } else {
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = (f16)0.f;
@@ -100,10 +101,10 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16* __restrict
 
 size_t packed_weight_elems(int N, int K) { return (size_t)((N + 31) / 32) * (K / kBK) * kWBlock; }
 
-void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, hipStream_t st) {
+void launch_pack_weight(const void* w_bf16, int N, int K, void* packed_f16, int32_t* status, hipStream_t st) {
   const size_t n_chunks = packed_weight_elems(N, K) / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, (const bf16*)w_bf16,
-                     N, K, (f16*)packed_f16, n_chunks);
+                     N, K, (f16*)packed_f16, n_chunks, status);
 }
 
 // ------------------------------------------------------------------ MFMA kernel (bf16 models)
@@ -123,7 +124,8 @@ template <int MT, int NT, int EPI>
 __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
-                                                        int m_blocks, int n_blocks, int n_split, int defer_rows) {
+                                                        int m_blocks, int n_blocks, int n_split, int defer_rows,
+                                                        int32_t* __restrict__ status) {
   // accumulators hold C^T tiles (SWAP): a lane owns one activation row and, per group of four
   // registers, four consecutive output columns, so the epilogue stores 8 or 16 bytes per lane
   using G = MfmaGemm<MT, NT, true>;
@@ -179,7 +181,6 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   G::run(acc, op, kt0, kt1, lds);
   if (defer_rows && n_rows_dev) M = min(*n_rows_dev, M_max);
 
-  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < MT; ++mi) {
@@ -190,10 +191,10 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
       f16* dst = (f16*)out + (size_t)m * N + n_wave0 + 4 * lg;
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        f16x4 v;
+        float y[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (f16)(silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][NT - 1][4 * i4 + j]);
-        *(f16x4*)(dst + 8 * i4) = v;
+        for (int j = 0; j < 4; ++j) y[j] = silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][NT - 1][4 * i4 + j];
+        *(f16x4*)(dst + 8 * i4) = to_f16x4_guarded(y[0], y[1], y[2], y[3], status);
       }
     } else {
 #pragma unroll
@@ -204,10 +205,8 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
         for (int i4 = 0; i4 < 4; ++i4) {
           const size_t o = (size_t)m * N + n0 + 8 * i4 + 4 * lg;
           if (EPI == EPI_STORE) {
-            f16x4 v;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (f16)acc[mi][ni][4 * i4 + j];
-            *(f16x4*)((f16*)out + o) = v;
+            *(f16x4*)((f16*)out + o) = to_f16x4_guarded(acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2],
+                                                        acc[mi][ni][4 * i4 + 3], status);
           } else {
             *(f32x4*)((float*)out + (size_t)split * M_max * N + o) =
                 f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
@@ -220,7 +219,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
 
 template <int MT, int NT, int EPI>
 static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
-                        const void* W, void* out, int n_split, hipStream_t st) {
+                        const void* W, void* out, int n_split, int32_t* status, hipStream_t st) {
   using G = MfmaGemm<MT, NT, true>;
   constexpr int nout = (EPI == EPI_SWIGLU) ? 4 * 32 : 4 * NT * 32;
   int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
@@ -229,7 +228,8 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   static bool attr_set = false;              // more than 64 KiB of dynamic LDS needs an opt-in (192-row tiles)
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
-                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split, total <= kOneRound ? 1 : 0);
+                     N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split, total <= kOneRound ? 1 : 0,
+                     status);
 }
 
 
@@ -239,7 +239,7 @@ template <int EPI>
 __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
                                                     const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                     const f16* __restrict__ Wp, void* __restrict__ out, int m_blocks,
-                                                    int n_blocks, int defer_rows) {
+                                                    int n_blocks, int defer_rows, int32_t* __restrict__ status) {
   using G = MfmaGemm8;
   extern __shared__ __align__(16) char lds[];
   int M = (!defer_rows && n_rows_dev) ? min(*n_rows_dev, M_max) : M_max;     // see gemm_mfma_kernel
@@ -285,7 +285,6 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
     G::run(acc, op, 0, nk, lds);
   if (defer_rows && n_rows_dev) M = min(*n_rows_dev, M_max);
 
-  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const int ln = lane & 31, lg = lane >> 5;
   const int n_wave0 = GLU ? (nb * 4 + wn) * 32 : (nb * 4 + wn) * 64;
 #pragma unroll
@@ -297,10 +296,10 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
       f16* dst = (f16*)out + (size_t)m * N + n_wave0 + 4 * lg;
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        f16x4 v;
+        float y[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (f16)(silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j]);
-        *(f16x4*)(dst + 8 * i4) = v;
+        for (int j = 0; j < 4; ++j) y[j] = silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j];
+        *(f16x4*)(dst + 8 * i4) = to_f16x4_guarded(y[0], y[1], y[2], y[3], status);
       }
     } else {
 #pragma unroll
@@ -308,12 +307,9 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
         const int n0 = n_wave0 + ni * 32;
         if (n0 >= N) continue;
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          f16x4 v;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = (f16)acc[mi][ni][4 * i4 + j];
-          *(f16x4*)((f16*)out + (size_t)m * N + n0 + 8 * i4 + 4 * lg) = v;
-        }
+        for (int i4 = 0; i4 < 4; ++i4)
+          *(f16x4*)((f16*)out + (size_t)m * N + n0 + 8 * i4 + 4 * lg) =
+              to_f16x4_guarded(acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3], status);
       }
     }
   }
@@ -321,7 +317,7 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
 
 template <int EPI>
 static void launch_gemm8(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
-                         const void* W, void* out, hipStream_t st) {
+                         const void* W, void* out, int32_t* status, hipStream_t st) {
   using G = MfmaGemm8;
   constexpr int nout = (EPI == EPI_SWIGLU) ? 128 : 256;
   const int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout;
@@ -329,7 +325,7 @@ static void launch_gemm8(const int32_t* n_rows_dev, int M_max, int N, int K, con
   static bool attr_set = false;
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm8_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm8_kernel<EPI>), dim3(grid), dim3(512), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
-                     (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, m_blocks * n_blocks <= kOneRound ? 1 : 0);
+                     (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, m_blocks * n_blocks <= kOneRound ? 1 : 0, status);
 }
 
 // The eight-wave kernel addresses both matrices with 32-bit byte offsets and pays off when 192-row blocks fit
@@ -361,16 +357,12 @@ static int pick_mt(int M_max) {
 
 template <int EPI>
 static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
-                    const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
+                    const int32_t* a_rows, const void* W, void* out, int32_t* status, hipStream_t st) {
   if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return 0; }
-  static const char* env_split = getenv("BS_GEMM_SPLIT");          // tuning aids
-  static const char* env_nt = getenv("BS_GEMM_NT");
-  static const char* env_mt = getenv("BS_GEMM_MT");
-  static const char* env_g8 = getenv("BS_GEMM8");
   bool small_tiles = false;
-  if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE) {
-    bool want = env_g8 ? atoi(env_g8) != 0 : (EPI == EPI_SWIGLU);
-    if (EPI == EPI_SWIGLU && !env_g8 && !env_mt && M_max > 128) {
+  if constexpr (EPI == EPI_SWIGLU) {
+    bool want = true;
+    if (M_max > 128) {
       // 192-row tiles, one workgroup per CU, against 96-row tiles, two per CU: whichever needs less time by rounds of
       // the 256 CUs.  In a single round the small tiles are about 10 % slower per unit of work; over several rounds
       // they are faster, because one workgroup's pipeline fill and epilogue overlap the other's main loop.
@@ -381,8 +373,8 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
       const long cost6 = r6 * 60, cost3 = r3 * (r3 > 1 ? 57 : 66);
       if (cost3 < cost6) { want = false; small_tiles = true; }
     }
-    if (want && gemm8_applies(M_max, N, K, EPI == EPI_SWIGLU ? 2 * N : N)) {
-      launch_gemm8<EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+    if (want && gemm8_applies(M_max, N, K, 2 * N)) {
+      launch_gemm8<EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, status, st);
       return 1;
     }
   }
@@ -390,7 +382,6 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   // float32-epilogue GEMMs have narrow outputs (N = d or Nqkv): measured on MI355X at M = 576, smaller row
   // tiles with at most 4 K splits beat 192-row tiles with 7 splits (down projection 50 -> 33 us, O 17 -> 13 us)
   if ((EPI == EPI_RESID_ADD || EPI == EPI_STORE_F32) && M_max > 64) mt = (K / kBK <= 32) ? 2 : 4;
-  if (env_mt) mt = atoi(env_mt);
   const int m_blocks = (M_max + mt * 32 - 1) / (mt * 32);
   int nt = 2;
   if (EPI != EPI_SWIGLU) {
@@ -405,7 +396,6 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
       if (s2 > 1) blocks2 *= s2;
     }
     if (blocks2 < 200) nt = 1;
-    if (env_nt) nt = atoi(env_nt) == 1 ? 1 : 2;
   }
   const int nout = (EPI == EPI_SWIGLU) ? 128 : nt * 128;
   const int blocks = m_blocks * ((N + nout - 1) / nout);
@@ -414,13 +404,11 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
     const int nk = K / kBK;
     if (blocks < 160) n_split = (256 + blocks / 2) / blocks;
     if (n_split > nk / 4) n_split = nk / 4 > 0 ? nk / 4 : 1;       // at least 4 K tiles per split
-    if (env_split) n_split = atoi(env_split);
     if (n_split < 1) n_split = 1;
-    if (n_split > 4 && !env_split) n_split = 4;
-    if (n_split > kMaxGemmSplit) n_split = kMaxGemmSplit;
+    if (n_split > 4) n_split = 4;
     if (n_split > nk) n_split = nk;
   }
-#define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, st)
+#define BS_GEMM(MT_, NT_) launch_mfma<MT_, NT_, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, n_split, status, st)
   if constexpr (EPI != EPI_SWIGLU) {
     if (nt == 1) {
       switch (mt) { case 1: BS_GEMM(1, 1); break; case 2: BS_GEMM(2, 1); break; case 3: BS_GEMM(3, 1); break; case 4: BS_GEMM(4, 1); break; default: BS_GEMM(6, 1); }
@@ -433,11 +421,11 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
 }
 
 int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
-                const int32_t* a_rows, const void* W, void* out, hipStream_t st) {
+                const int32_t* a_rows, const void* W, void* out, int32_t* status, hipStream_t st) {
   switch (epi) {
-    case EPI_STORE: return dispatch<EPI_STORE>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
-    case EPI_RESID_ADD: return dispatch<EPI_RESID_ADD>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
-    case EPI_SWIGLU: return dispatch<EPI_SWIGLU>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
-    default: return dispatch<EPI_STORE_F32>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, st);
+    case EPI_STORE: return dispatch<EPI_STORE>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, status, st);
+    case EPI_RESID_ADD: return dispatch<EPI_RESID_ADD>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, status, st);
+    case EPI_SWIGLU: return dispatch<EPI_SWIGLU>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, status, st);
+    default: return dispatch<EPI_STORE_F32>(dtype, n_rows_dev, M_max, N, K, A, a_rows, W, out, status, st);
   }
 }

@@ -52,6 +52,18 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
         }
       }
     }
+    // token ids of the sequence's rows (the last token and the k drafts), a quarter per lane: a sequence with an id
+    // outside the vocabulary is skipped like one with a bad draft length (no row is embedded, appended or judged)
+    if (!(fault & BS_FAULT_DRAFT_LEN)) {
+      if (sub == 0 && last_token) {
+        const int t = last_token[b];
+        if (t < 0 || t >= vocab) fault |= BS_FAULT_TOKEN_ID;
+      }
+      for (int i = sub; i < k; i += 4) {
+        const int t = draft_tokens[(size_t)b * k_max + i];
+        if (t < 0 || t >= vocab) fault |= BS_FAULT_TOKEN_ID;
+      }
+    }
     fault |= __shfl_xor(fault, 1);
     fault |= __shfl_xor(fault, 2);
     if (sub == 0) {
@@ -97,13 +109,9 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
     int k = s_k[b];
     if (k < 0 || i > k) continue;
     int r = p.row_start[b] + i;
-    int tok = (i == 0) ? (last_token ? last_token[b] : 0) : draft_tokens[(size_t)b * k_max + i - 1];
-    if (tok < 0 || tok >= vocab) { atomicOr(&s_fault, BS_FAULT_TOKEN_ID); tok = 0; }
-    int tgt = -1;
-    if (i < k) {
-      tgt = draft_tokens[(size_t)b * k_max + i];
-      if (tgt < 0 || tgt >= vocab) tgt = 0;   // flagged when seen as an input token of row i+1
-    }
+    // every id was validated in phase 1 (a sequence with a bad one has s_k[b] = -1 and is skipped above)
+    const int tok = (i == 0) ? (last_token ? last_token[b] : 0) : draft_tokens[(size_t)b * k_max + i - 1];
+    const int tgt = (i < k) ? draft_tokens[(size_t)b * k_max + i] : -1;
     p.row_seq[r] = b;
     p.row_pos[r] = i;
     p.row_tok[r] = tok;
@@ -183,6 +191,16 @@ __global__ void commit_kernel(Plan p, KvView kv, int B, const int32_t* __restric
 
 __global__ void clear_status_kernel(int32_t* status) { *status = 0; }
 
+// out[b] = committed length of slot seq_slot[b] (-1 and BS_FAULT_SLOT for a slot outside the cache)
+__global__ void kv_lengths_kernel(KvView kv, int B, const int32_t* __restrict__ seq_slot, int32_t* __restrict__ out,
+                                  int32_t* __restrict__ status) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int slot = seq_slot[b];
+  if (slot < 0 || slot >= kv.n_slots) { out[b] = -1; atomicOr(status, BS_FAULT_SLOT); return; }
+  out[b] = kv.ctx_len[slot];
+}
+
 void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, const int32_t* seq_slot,
                  const int32_t* last_token, const int32_t* draft_tokens, const int32_t* draft_len,
                  bool need_kv, int attn_s_min, int attn_force_chunks, int n_layers, hipStream_t st) {
@@ -192,6 +210,9 @@ void launch_plan(const Plan& p, const KvView& kv, int B, int k_max, int vocab, c
 void launch_commit(const Plan& p, const KvView& kv, int B, const int32_t* seq_slot, const int32_t* n_commit,
                    hipStream_t st) {
   hipLaunchKernelGGL(commit_kernel, dim3((B + 255) / 256), dim3(256), 0, st, p, kv, B, seq_slot, n_commit);
+}
+void launch_kv_lengths(const KvView& kv, int B, const int32_t* seq_slot, int32_t* out, int32_t* status, hipStream_t st) {
+  hipLaunchKernelGGL(kv_lengths_kernel, dim3((B + 255) / 256), dim3(256), 0, st, kv, B, seq_slot, out, status);
 }
 void launch_clear_status(int32_t* status, hipStream_t st) {
   hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);

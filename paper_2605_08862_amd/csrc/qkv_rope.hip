@@ -11,7 +11,6 @@
 // v are still rounded exactly once, after the rotation.  Replaces a split-K GEMM + a separate rotary kernel
 // that had to sum the float32 slabs (13.5 + 8 us at M = 576, d = 1536 against about 15 us fused).
 #include "gemm_mfma.h"
-#include <stdlib.h>
 
 namespace {
 constexpr int kD = 128;
@@ -72,7 +71,6 @@ qkv_rope_kernel(Plan p, KvView kv, int M_max, int K, int Hq, int Hkv, const f16*
             f32x4{acc[mi][0][4 * i4], acc[mi][0][4 * i4 + 1], acc[mi][0][4 * i4 + 2], acc[mi][0][4 * i4 + 3]};
     __syncthreads();
   }
-  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   const float sign = (wave < 2) ? -1.0f : 1.0f;       // y1 = x1 c - x2 s (columns < 64), y2 = x2 c + x1 s
   const int partner = (wave < 2) ? 64 : -64;
 #pragma unroll
@@ -103,19 +101,16 @@ qkv_rope_kernel(Plan p, KvView kv, int M_max, int K, int Hq, int Hkv, const f16*
         for (int e = 0; e < 4; ++e) y[e] = acc[mi][0][4 * i4 + e] * c[e] + sign * other[e] * sn[e];
       }
       if (head < Hq) {
-        f16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (f16)y[e];
-        *(f16x4*)(q_out + ((size_t)m * Hq + head) * kD + d) = v;
-      } else if (!is_v) {
-        f16x4 v;                                      // bf16-rounded value in float16 encoding (page format)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (f16)(float)(bf16)y[e];
-        *(f16x4*)(k_pages + pbase + k_index_bf16(kD, head - Hq, tok, d)) = v;
+        *(f16x4*)(q_out + ((size_t)m * Hq + head) * kD + d) = to_f16x4_guarded(y[0], y[1], y[2], y[3], p.status);
       } else {
+        // bf16-rounded values in float16 encoding (page format)
+        const f16x4 v = to_f16x4_guarded((float)(bf16)y[0], (float)(bf16)y[1], (float)(bf16)y[2], (float)(bf16)y[3], p.status);
+        if (!is_v) {
+          *(f16x4*)(k_pages + pbase + k_index_bf16(kD, head - Hq, tok, d)) = v;
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          v_pages[pbase + v_index_bf16(kD, head - Hq - Hkv, tok, d + e)] = (f16)(float)(bf16)y[e];
+          for (int e = 0; e < 4; ++e) v_pages[pbase + v_index_bf16(kD, head - Hq - Hkv, tok, d + e)] = v[e];
+        }
       }
     }
   }
@@ -142,12 +137,10 @@ bool qkv_rope_supported(const Shape& s) { return s.dtype == BS_BF16 && s.D == kD
 
 void launch_qkv_rope(const Shape& s, const Plan& p, const KvView& kv, int M_max, const void* A, const void* Wp,
                      const float* cos_t, const float* sin_t, void* q_out, void* k_pages, void* v_pages, hipStream_t st) {
-  static const char* env_mt = getenv("BS_QKV_MT");                 // tuning aid
   // 32-row tiles while that gives at most two workgroups per CU (measured at M = 576, 16 heads: 13.5 us
   // against 15.3 us with 64-row tiles); larger tiles re-read the weights less often when there are many rows
   const int tiles1 = (M_max + 31) / 32 * (s.Hq + 2 * s.Hkv);
-  int mt = tiles1 <= 512 ? 1 : (tiles1 <= 2048 ? 2 : 4);
-  if (env_mt) mt = atoi(env_mt);
+  const int mt = tiles1 <= 512 ? 1 : (tiles1 <= 2048 ? 2 : 4);
   if (mt <= 1) launch_t<1>(s, p, kv, M_max, A, Wp, cos_t, sin_t, q_out, k_pages, v_pages, st);
   else if (mt == 2) launch_t<2>(s, p, kv, M_max, A, Wp, cos_t, sin_t, q_out, k_pages, v_pages, st);
   else launch_t<4>(s, p, kv, M_max, A, Wp, cos_t, sin_t, q_out, k_pages, v_pages, st);

@@ -7,7 +7,6 @@
 //            recomputed by the same MFMA loop (bit-identical logits) and sampled by inverse CDF in
 //            vocabulary order with float64 running sums (Eq. 3 / max(0, p - q)).
 #include "gemm_mfma.h"
-#include <stdlib.h>
 
 enum { MODE_NONE = 0, MODE_PLAIN = 1, MODE_RESID_ONEHOT = 2, MODE_RESID_DENSE = 3 };
 
@@ -676,14 +675,12 @@ static void launch_lmhead_any(const Shape& s, const int32_t* n_rows_dev, int M_m
   // 96-row tile is used: it fits two workgroups per CU, and the statistics epilogue and the pipeline fill of
   // one overlap the matrix products of the other (measured at M = 576, V = 151936: 308 us against 372 us with
   // 192-row tiles, one workgroup per CU).
-  static const char* env_mt = getenv("BS_LM_MT");                  // tuning aid
-  const int mt = env_mt ? atoi(env_mt) : (M_max <= 32 ? 1 : M_max <= 64 ? 2 : M_max <= 128 ? 4 : 3);
+  const int mt = M_max <= 32 ? 1 : M_max <= 64 ? 2 : M_max <= 128 ? 4 : 3;
 #define BS_LM(MT_) launch_lmhead_t<MT_, STATS>(s, n_rows_dev, M_max, hf, x_rows, lm_head, inv_temp, row_target, sb, store, st)
   switch (mt) {
     case 1: BS_LM(1); break;
     case 2: BS_LM(2); break;
     case 4: BS_LM(4); break;
-    case 6: BS_LM(6); break;
     default: BS_LM(3);
   }
 #undef BS_LM

@@ -134,6 +134,11 @@ class Engine:
     def kv_commit(self, seq_slot, n_commit):
         B.bs_kv_commit(self.ctx, seq_slot.numel(), seq_slot, n_commit)
 
+    def kv_lengths(self, seq_slot):
+        out = torch.empty(seq_slot.numel(), dtype=torch.int32, device=self.device)
+        B.bs_kv_lengths(self.ctx, seq_slot.numel(), seq_slot, out)
+        return out
+
     def kv_write(self, layer, slot, pos0, k_rows, v_rows):
         B.bs_kv_write(self.ctx, layer, slot, pos0, k_rows.shape[0], k_rows.contiguous(), v_rows.contiguous())
 

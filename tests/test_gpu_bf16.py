@@ -245,3 +245,55 @@ def test_lookup_to_commit_without_host_sync():
     n_acc = out["n_accepted"].cpu().numpy()
     assert eng.ctx_len.cpu().tolist() == [ctx + int(n) + 1 for n in n_acc]
     eng.close()
+
+
+@pytest.mark.parametrize("which", ["w_gate_up", "wq_wk", "lm_head_weight", "kv_import"])
+def test_float16_range_is_guarded(which):
+    """bf16 models compute with float16 matrix operands (largest finite value 65504).  A weight matrix scaled so
+    that a producer of such an operand overflows must end in saturated, finite results and BS_FAULT_RANGE in the
+    status word: gated MLP activation (SwiGLU epilogue), rotated q and appended k (QKV epilogue), a weight beyond
+    the range at packing time, and imported K/V rows."""
+    desc = W.shape("mini_bf16")
+    w = W.make_weights(desc, seed=41)
+    kv_scale = 1.0
+    if which == "w_gate_up":
+        for lw in w["layers"]:
+            lw["w_gate"] = (lw["w_gate"].float() * 2000).to(torch.bfloat16)
+            lw["w_up"] = (lw["w_up"].float() * 2000).to(torch.bfloat16)
+    elif which == "wq_wk":
+        for lw in w["layers"]:
+            lw["wq"] = (lw["wq"].float() * 2e5).to(torch.bfloat16)
+            lw["wk"] = (lw["wk"].float() * 2e5).to(torch.bfloat16)
+    elif which == "lm_head_weight":
+        w["lm_head"][3, 5] = 1e6            # a bf16 value float16 cannot hold
+    else:
+        kv_scale = 1e6
+    Bn, k_max = 3, 4
+    eng = Engine(desc, fuse_weights(w, desc["dtype"], DEV), Bn, 256, B_max=Bn, k_max=k_max)
+    torch.cuda.synchronize()
+    st0 = eng.poll_status()
+    assert (st0 == B.BS_FAULT_RANGE) == (which == "lm_head_weight"), st0       # set while packing, and only then
+    for b in range(Bn):
+        for l, (k, v) in enumerate(W.context_kv(desc, 70, 4100 + b)):
+            eng.kv_write(l, b, 0, (k.float() * kv_scale).to(torch.bfloat16).to(DEV), v.to(DEV))
+    if which == "kv_import":
+        assert eng.poll_status() == B.BS_FAULT_RANGE
+    eng.ctx_len.fill_(70)
+    rng = np.random.default_rng(41)
+    drafts = H.dev_i32(rng.integers(0, desc["vocab"], (Bn, k_max)))
+    dl = H.dev_i32([4, 0, 2])
+    slots = H.dev_i32(np.arange(Bn))
+    logits = eng.verify_step(slots, H.dev_i32(rng.integers(0, desc["vocab"], Bn)), drafts, dl, k_max, want_logits=True)
+    ua, us = W.uniforms(42, Bn, k_max)
+    out = eng.accept_resample(drafts, dl, k_max, H.dev_f32(ua), H.dev_f32(us))
+    eng.kv_commit(slots, out["n_accepted"] + 1)
+    st = eng.poll_status()
+    if which in ("w_gate_up", "wq_wk"):
+        assert st == B.BS_FAULT_RANGE, st
+    else:
+        assert st == 0, st                  # the saturated weight / cache rows are ordinary finite operands
+    got = logits[:9].cpu().numpy()             # M = 5 + 1 + 3 packed rows
+    assert np.isfinite(got).all()
+    n_emit = out["n_emitted"].cpu().numpy()
+    assert ((n_emit >= 1) & (n_emit <= k_max + 1)).all()
+    eng.close()

@@ -138,10 +138,32 @@ def test_device_faults_are_flagged_not_fatal():
     last = H.dev_i32([1, 2, 3, desc["vocab"] + 5])               # bad token id
     drafts = H.dev_i32(np.zeros((4, 4)))
     dl = H.dev_i32([4, 9, 0, 1])                                 # 9 > k_max
+    eng.ctx_len.copy_(H.dev_i32([10, 11, 12, 13]))
     eng.verify_step(slots, last, drafts, dl, 4)
+    ua, us = W.uniforms(5, 4, 4)
+    out = eng.accept_resample(drafts, dl, 4, H.dev_f32(ua), H.dev_f32(us))
+    eng.kv_commit(slots, out["n_accepted"] + 1)
     st = eng.poll_status()
     assert st & B.BS_FAULT_DRAFT_LEN and st & B.BS_FAULT_TOKEN_ID
     assert eng.poll_status() == 0                                # cleared
+    # the two offending sequences (1: draft length, 3: token id) were skipped altogether, the others stepped
+    n_emit, n_acc = out["n_emitted"].cpu().numpy(), out["n_accepted"].cpu().numpy()
+    toks = out["out_tokens"].cpu().numpy()
+    assert n_emit[1] == 0 and n_emit[3] == 0 and n_acc[1] == 0 and n_acc[3] == 0
+    assert (toks[1] == -1).all() and (toks[3] == -1).all()
+    assert n_emit[0] >= 1 and n_emit[2] == 1
+    got_len = eng.kv_lengths(slots).cpu().tolist()
+    assert got_len == eng.ctx_len.cpu().tolist() == [10 + int(n_acc[0]) + 1, 11, 12 + 1, 13]
+    # a bad draft token (not only a bad last token) also skips its sequence; a bad token beyond k_b is never read
+    drafts_bad = H.dev_i32([[0, -7, 0, 0], [0, 0, 0, 0], [0, 0, desc["vocab"], 0], [5, 5, 5, 5]])
+    eng.verify_step(slots, H.dev_i32([1, 2, 3, 4]), drafts_bad, H.dev_i32([4, 4, 2, 4]), 4)
+    out = eng.accept_resample(drafts_bad, H.dev_i32([4, 4, 2, 4]), 4, H.dev_f32(ua), H.dev_f32(us))
+    assert eng.poll_status() == B.BS_FAULT_TOKEN_ID
+    n_emit = out["n_emitted"].cpu().numpy()
+    assert n_emit[0] == 0 and n_emit[1] >= 1 and n_emit[2] >= 1 and n_emit[3] >= 1
+    # bs_kv_lengths: batch order, bad slot -> -1 + fault
+    assert eng.kv_lengths(H.dev_i32([3, 0, 77])).cpu().tolist() == [13, 10 + int(n_acc[0]) + 1, -1]
+    assert eng.poll_status() == B.BS_FAULT_SLOT
     eng.ctx_len.fill_(320 - 2)                                   # not enough room for k+1 rows
     eng.verify_step(slots, H.dev_i32([1, 2, 3, 4]), drafts, H.dev_i32([4, 4, 4, 4]), 4)
     assert eng.poll_status() & B.BS_FAULT_KV_PAGES

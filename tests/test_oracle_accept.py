@@ -240,7 +240,50 @@ def test_paper_metric_identities():
         assert abs((acc_len - 1) / draft_len * 100 - rate) < 0.15
     mean = sum(n * w for n, w in hist)
     assert abs(mean - rows[0][0]) < 0.01
-    s0, s1, t0, t1, reported = eq1
+    # Eq. 1 with alpha from the (maximum) step counts and mu from Tab. 6's INDEPENDENTLY measured per-step latency
+    # against the plain-decode latency time / steps.  (With mu also taken from the two rollout times the expression
+    # collapses to t1 / t0 whatever the step counts are, which would check nothing.)  This cross-checks the paper's
+    # tables and the meaning of alpha and mu; it pins no oracle function.
+    s0, s1, t0, t1, ms_step, reported = eq1
     alpha = 1 - s1 / s0
-    mu = (t1 / s1) / (t0 / s0) - 1
-    assert abs((1 - (1 - alpha) * (1 + mu)) * 100 - reported) < 0.15
+    mu = ms_step / (t0 / s0 * 1e3) - 1
+    assert abs(alpha * 100 - 59.6) < 0.2                            # Tab. 2's printed step reduction
+    assert abs(t1 / s1 * 1e3 - ms_step) / ms_step < 0.01              # rollout time / max steps == Tab. 6 latency
+    assert abs((1 - (1 - alpha) * (1 + mu)) * 100 - reported) < 0.5
+
+
+def test_verify_batch_packs_rows_like_per_sequence_calls():
+    """verify_batch only slices packed rows: sequence b owns logits rows row0_b .. row0_b + k_b with row0_b =
+    sum_{b'<b}(k_b' + 1) and proposal rows d0_b .. d0_b + k_b - 1 with d0_b = sum_{b'<b} k_b'.  Hand-packed ragged
+    batch (k_b = 0 first, in the middle and last) against per-sequence calls with the offsets written out by hand;
+    every row is made distinguishable so that an off-by-one in either offset changes a result."""
+    rng = np.random.default_rng(77)
+    V, k_max = 23, 5
+    k_b = [0, 3, 0, 5, 1, 0]
+    row0 = [0, 1, 5, 6, 12, 14]                 # by hand: cumulative (k_b + 1)
+    d0 = [0, 0, 3, 3, 8, 9]                     # by hand: cumulative k_b
+    M, Td = 15, 9
+    assert row0[-1] + k_b[-1] + 1 == M and d0[-1] + k_b[-1] == Td
+    z = rng.normal(0, 2.0, (M, V))
+    ql = rng.normal(0, 2.0, (Td, V))
+    drafts = rng.integers(0, V, (len(k_b), k_max))
+    for b, k in enumerate(k_b):                 # make most drafts likely so that accept / reject both occur
+        for j in range(k):
+            if rng.random() < 0.7:
+                drafts[b, j] = int(np.argmax(z[row0[b] + j] + ql[d0[b] + j]))
+    ua = rng.random((len(k_b), k_max))
+    us = rng.random(len(k_b))
+    for q_rows in (None, ql):
+        for kw in (dict(), dict(temperature=0.7, emit_bonus=False), dict(temperature=0.0), dict(eos_id=int(drafts[3, 1]))):
+            got = A.verify_batch(z, drafts, k_b, ua, us, q_rows, **kw)
+            assert len(got) == len(k_b)
+            for b, k in enumerate(k_b):
+                want = A.verify_sequence(z[row0[b]:row0[b] + k + 1], drafts[b][:k], ua[b], us[b],
+                                         None if q_rows is None else q_rows[d0[b]:d0[b] + k], **kw)
+                assert got[b].n_accepted == want.n_accepted and got[b].tokens == want.tokens
+                assert got[b].accept_gap == want.accept_gap and got[b].sample_margin == want.sample_margin
+                assert got[b].sampled_row == want.sampled_row
+    # a shifted offset must be visible: feeding sequence 3 the rows of an off-by-one packing changes its result
+    shifted = A.verify_sequence(z[row0[3] - 1:row0[3] + k_b[3]], drafts[3][:k_b[3]], ua[3], us[3], ql[d0[3]:d0[3] + k_b[3]])
+    base = A.verify_batch(z, drafts, k_b, ua, us, ql)[3]
+    assert shifted.accept_gap != base.accept_gap
