@@ -204,6 +204,23 @@ bs_status bs_accept_resample_logits(bs_ctx* ctx, int B, int vocab, const float* 
                                     int32_t* n_accepted, int32_t* out_tokens, int32_t* n_emitted,
                                     uint32_t* near_tie, void* stream);
 
+/* For callers that cannot allocate or hold device memory for the library: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same rule, same arguments and same results as
+ * bs_accept_resample_logits with the filter off, but with no context and no workspace: what the kernels keep between
+ * launches (row packing, softmax statistics, sampling partials) lives in a 9 MiB device array built into the
+ * library (one copy per GPU, held until the process ends).  The call allocates nothing and only enqueues kernels on
+ * `stream` (the stream's device must be the current device).  Limits: B <= 1024, B * (k_max + 1) <= 2048 packed
+ * rows, k_max <= BS_MAX_K, 2 <= vocab <= 262144; beyond them BS_ESHAPE.  A sequence whose draft_len or token ids are
+ * out of range is skipped (n_accepted = n_emitted = 0, out_tokens = -1); there is no status word to poll.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or host
+ * threads) race; calls ordered on one stream do not.  Errors: BS_EINVAL (null, temperature < 0, bad q_dtype),
+ * BS_ESHAPE, BS_EHIP (the array's address could not be obtained). */
+bs_status bs_accept_resample_logits_noalloc(int B, int vocab, const float* logits, const int32_t* draft_tokens,
+                                            const int32_t* draft_len, int k_max, const void* q_logits, int q_dtype,
+                                            float temperature, int eos_id, int emit_bonus, const float* u_accept,
+                                            const float* u_sample, int32_t* n_accepted, int32_t* out_tokens,
+                                            int32_t* n_emitted, uint32_t* near_tie, void* stream);
+
 /* Sec. 3.2 defines p_t as the decoding distribution "after temperature scaling and any top-p / top-k
  * filtering": selects that filtering for all following bs_accept_resample / bs_accept_resample_logits
  * calls of the context.  Tokens are ranked by logit (equal logits: lower index first); top_k keeps the

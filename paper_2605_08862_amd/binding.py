@@ -19,7 +19,7 @@ STATUS_NAMES = ["BS_OK", "BS_EINVAL", "BS_ESHAPE", "BS_ECAPACITY", "BS_ESTATE", 
 EXPORTS = ["bs_workspace_bytes", "bs_create", "bs_destroy", "bs_last_error", "bs_pool_bind", "bs_draft_lookup",
            "bs_verify_step", "bs_accept_resample", "bs_accept_resample_logits", "bs_kv_commit", "bs_kv_write",
            "bs_kv_read", "bs_poll_status", "bs_profile_begin", "bs_profile_end", "bs_index_build", "bs_index_free",
-           "bs_index_bind", "bs_set_filter", "bs_kv_lengths"]
+           "bs_index_bind", "bs_set_filter", "bs_kv_lengths", "bs_accept_resample_logits_noalloc"]
 PROF_CLASSES = {"attention": 1, "gemm_qkv": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5, "lmhead": 6,
                 "sample": 7, "lookup": 8, "empty": 9}
 
@@ -73,6 +73,8 @@ def lib():
         L.bs_accept_resample.argtypes = [vp, i32, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.bs_accept_resample_logits.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp,
                                                 vp, vp, vp, vp]
+        L.bs_accept_resample_logits_noalloc.argtypes = [i32, i32, vp, vp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp,
+                                                        vp, vp, vp, vp]
         L.bs_set_filter.argtypes = [vp, i32, f32, vp]
         L.bs_kv_commit.argtypes = [vp, i32, vp, vp, vp]
         L.bs_kv_lengths.argtypes = [vp, i32, vp, vp, vp]
@@ -207,6 +209,16 @@ def bs_accept_resample_logits(ctx, B, vocab, logits, draft_tokens, draft_len, k_
                                                 k_max, _ptr(q_logits), q_dtype, temperature, eos_id, int(emit_bonus),
                                                 _ptr(u_accept), _ptr(u_sample), _ptr(n_accepted), _ptr(out_tokens),
                                                 _ptr(n_emitted), _ptr(near_tie), _stream()))
+
+
+def bs_accept_resample_logits_noalloc(B, vocab, logits, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature,
+                                      eos_id, emit_bonus, u_accept, u_sample, n_accepted, out_tokens, n_emitted, near_tie):
+    st = lib().bs_accept_resample_logits_noalloc(B, vocab, _ptr(logits), _ptr(draft_tokens), _ptr(draft_len), k_max,
+                                                 _ptr(q_logits), q_dtype, temperature, eos_id, int(emit_bonus),
+                                                 _ptr(u_accept), _ptr(u_sample), _ptr(n_accepted), _ptr(out_tokens),
+                                                 _ptr(n_emitted), _ptr(near_tie), _stream())
+    if st != BS_OK:
+        raise BsError(st, "bs_accept_resample_logits_noalloc")
 
 
 def bs_set_filter(ctx, top_k, top_p, logits_scratch):

@@ -1,6 +1,7 @@
 // C ABI of libbubblespec: argument validation, workspace carving and kernel sequencing of one
 // speculative-verification step (Alg. 1 of the paper; see include/bubblespec.h for the contract).
 #include "common.h"
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -593,6 +594,81 @@ bs_status bs_poll_status(bs_ctx* c, void* stream, int32_t* fault_out) {
   launch_clear_status(c->plan.status, st);
   *fault_out = host;
   return check_hip(c);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Allocation-free variant of bs_accept_resample_logits (see the header).  Everything the sampler kernels keep
+// between launches (the device plan of the packed rows, per-tile and per-row softmax statistics, the float64
+// sampling partials) lives in g_noalloc_scratch, a file-scope device array, instead of a caller-supplied workspace.
+// The array's name is only a host-side handle: its device address is obtained once per device with
+// hipGetSymbolAddress and that address is what is carved and handed to the kernels.
+constexpr int kNoAllocMaxB = 1024;                       // sequences per call
+constexpr int kNoAllocMaxRows = 2048;                    // packed rows B * (k_max + 1) per call
+constexpr int kNoAllocMaxVocab = 262144;
+constexpr size_t kNoAllocScratchBytes = (size_t)9 << 20; // 9 MiB per device, held until the process ends
+constexpr int kNoAllocMaxDevices = 64;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocScratchBytes];
+
+namespace {
+struct NoAllocState {
+  bs_ctx* ctx = nullptr;       // host-side view of this device's copy of the array (never freed)
+};
+NoAllocState g_noalloc[kNoAllocMaxDevices];
+std::mutex g_noalloc_mutex;
+
+// Host-side view of the current device's scratch array, created at the first call on that device.
+bs_status noalloc_state(bs_ctx** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNoAllocMaxDevices) return BS_EHIP;
+  std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+  if (!g_noalloc[dev].ctx) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return BS_EHIP;
+    }
+    bs_ctx* c = new (std::nothrow) bs_ctx();
+    if (!c) return BS_ECAPACITY;
+    c->s = Shape{1, 64, 1, 1, 64, 64, kNoAllocMaxVocab, BS_F32, 1e-6f, 1e6f};   // only V and dtype are consulted
+    c->B_max = kNoAllocMaxB;
+    c->k_max = BS_MAX_K;
+    c->M_max = kNoAllocMaxRows;
+    c->kv = KvView{0, 0, 0, nullptr, nullptr};
+    for (int pass = 0; pass < 2; ++pass) {               // measure, then lay out
+      Carver w{pass ? (char*)ptr : nullptr};
+      carve_plan(w, c->plan, kNoAllocMaxB, kNoAllocMaxRows, false, 0);
+      carve_sampler(w, c->sb, kNoAllocMaxB, kNoAllocMaxRows, (kNoAllocMaxVocab + 1023) / 1024);
+      if (w.off > kNoAllocScratchBytes) { delete c; return BS_ECAPACITY; }
+    }
+    g_noalloc[dev].ctx = c;
+  }
+  *out = g_noalloc[dev].ctx;
+  return BS_OK;
+}
+}  // namespace
+
+bs_status bs_accept_resample_logits_noalloc(int B, int vocab, const float* logits, const int32_t* draft_tokens,
+                                            const int32_t* draft_len, int k_max, const void* q_logits, int q_dtype,
+                                            float temperature, int eos_id, int emit_bonus, const float* u_accept,
+                                            const float* u_sample, int32_t* n_accepted, int32_t* out_tokens,
+                                            int32_t* n_emitted, uint32_t* near_tie, void* stream) {
+  if (!logits || !draft_len || (k_max > 0 && (!draft_tokens || !u_accept)) || !u_sample || !n_accepted || !out_tokens ||
+      !n_emitted || !near_tie)
+    return BS_EINVAL;
+  if (!(temperature >= 0.f)) return BS_EINVAL;
+  if (q_logits && q_dtype != BS_F32 && q_dtype != BS_BF16) return BS_EINVAL;
+  if (B < 1 || B > kNoAllocMaxB || k_max < 0 || k_max > BS_MAX_K || (long)B * (k_max + 1) > kNoAllocMaxRows ||
+      vocab < 2 || vocab > kNoAllocMaxVocab)
+    return BS_ESHAPE;                                    // beyond the fixed maximum of the static scratch
+  bs_ctx* c = nullptr;
+  const bs_status st = noalloc_state(&c);
+  if (st != BS_OK) return st;
+  // The array keeps the previous call's contents.  The only word a call relies on being zero is the status word
+  // (the plan and the statistics are written before they are read); it is cleared by a kernel, not a memset node,
+  // so that the call can be captured into a HIP graph.
+  launch_clear_status(c->plan.status, (hipStream_t)stream);
+  return accept_common(c, B, vocab, logits, draft_tokens, draft_len, k_max, q_logits, q_dtype, temperature, eos_id,
+                       emit_bonus, u_accept, u_sample, n_accepted, out_tokens, n_emitted, near_tie, (hipStream_t)stream);
 }
 
 // Not part of the public ABI: selects the unfused QKV path (projection GEMM, then the rotary / append kernel)
