@@ -28,7 +28,11 @@ def fuse_weights(w, dtype, device):
 class Engine:
     """Owns the device buffers of one context and forwards to the C ABI."""
 
-    def __init__(self, desc, weights, n_slots, max_ctx, B_max, k_max, device="cuda:0", page_perm_seed=None):
+    def __init__(self, desc, weights, n_slots, max_ctx, B_max, k_max, device="cuda:0", page_perm_seed=None,
+                 slot_tokens=None):
+        """max_ctx: token capacity of every slot; slot_tokens (optional, one entry per slot) gives every slot its own
+        capacity instead, so that a ragged batch only takes the pages it needs (block-table entries beyond a slot's
+        pages are -1)."""
         self.desc = dict(desc)
         self.device = torch.device(device)
         self.cdesc = B.make_desc(desc)
@@ -37,9 +41,12 @@ class Engine:
         # page encoding: float32 models store float32; bf16 models store bf16-rounded values as float16 bits
         td = torch.float32 if desc["dtype"] == B.BS_F32 else torch.float16
         P = B.BS_PAGE_TOKENS
-        self.max_pages = (max_ctx + P - 1) // P
+        caps = [int(max_ctx)] * n_slots if slot_tokens is None else [int(t) for t in slot_tokens]
+        assert len(caps) == n_slots
+        pages_of = [(c + P - 1) // P for c in caps]
+        self.max_pages = max(pages_of)
         self.n_slots = n_slots
-        self.n_pages = n_slots * self.max_pages
+        self.n_pages = sum(pages_of)
         page_elems = desc["n_kv_heads"] * P * desc["head_dim"]
         # pages are zero-initialised: masked positions still enter the P*V product with weight 0
         self.k_pages = [torch.zeros(self.n_pages, page_elems, dtype=td, device=self.device)
@@ -50,7 +57,12 @@ class Engine:
         if page_perm_seed is not None:      # scatter pages to exercise the block table
             g = torch.Generator().manual_seed(page_perm_seed)
             ids = ids[torch.randperm(self.n_pages, generator=g)]
-        self.block_table = ids.view(n_slots, self.max_pages).contiguous().to(self.device)
+        table = torch.full((n_slots, self.max_pages), -1, dtype=torch.int32)
+        at = 0
+        for b, n in enumerate(pages_of):
+            table[b, :n] = ids[at:at + n]
+            at += n
+        self.block_table = table.contiguous().to(self.device)
         self.ctx_len = torch.zeros(n_slots, dtype=torch.int32, device=self.device)
         nbytes = B.bs_workspace_bytes(self.cdesc, B_max, k_max)
         if nbytes == 0:

@@ -113,3 +113,93 @@ def device_kept(z_row_f32, f_key, f_idx):
     key = np.where(u & 0x80000000, (~u) & 0xffffffff, u | 0x80000000)
     j = np.arange(z.shape[0])
     return np.flatnonzero((key > int(f_key)) | ((key == int(f_key)) & (j <= int(f_idx))))
+
+
+def oracle_weights_f64(w):
+    """float64 copies of the matrices (the embedding stays float32: only single rows of it are read)."""
+    wn = W.weights_to_numpy(w)
+    c = lambda a: np.asarray(a, dtype=np.float64)
+    return {"embed": wn["embed"], "lm_head": c(wn["lm_head"]), "final_norm": c(wn["final_norm"]),
+            "layers": [{k: c(v) for k, v in lw.items()} for lw in wn["layers"]]}
+
+
+def sample_sequences(ctx, k_b, k_max):
+    pick = [int(np.argmin(ctx)), int(np.argmax(ctx))]
+    zero = np.flatnonzero(k_b == 0)
+    full = np.flatnonzero(k_b == k_b.max())
+    if len(zero):
+        pick.append(int(zero[0]))
+    if len(full):
+        pick.append(int(full[-1]))
+    return sorted(set(pick))
+
+
+def run_bench_workload_case(name, layers=None):
+    """One step of a bench.py workload (optionally cut to `layers` layers) through all three tiers; see
+    tests/test_gpu_launch_sizes.py.  Returns (workload, statistics, (drafts, k_b))."""
+    import bench
+    wl = bench.build_workload(name, layers=layers)
+    eng, desc, Bn, k_max = wl["eng"], wl["desc"], wl["B"], wl["k_max"]
+    ctx = np.asarray(wl["ctx"])
+    eng.ctx_len.copy_(wl["ctx0"])
+    if wl["drafts"] is None:                               # configuration 5: drafts straight from the device lookup
+        dt, dl = eng.draft_lookup(wl["seq_prompt"], wl["tails"], 4, 1, k_max)
+    else:
+        dt, dl = wl["drafts"], wl["draft_len"]
+    logits = eng.verify_step(wl["slots"], wl["last"], dt, dl, k_max, want_logits=True)
+    out = eng.accept_resample(dt, dl, k_max, wl["ua"], wl["us"], q_logits=wl["q_logits"])
+    eng.kv_commit(wl["slots"], out["n_accepted"] + 1)
+    assert eng.poll_status() == 0
+    k_b = dl.cpu().numpy().astype(np.int64)
+    drafts = dt.cpu().numpy()
+    n_acc, n_emit = out["n_accepted"].cpu().numpy(), out["n_emitted"].cpu().numpy()
+    toks = out["out_tokens"].cpu().numpy()
+    # ---- properties that hold at any size
+    assert eng.ctx_len.cpu().tolist() == [int(c) + int(n) + 1 for c, n in zip(ctx, n_acc)]
+    assert eng.kv_lengths(wl["slots"]).cpu().tolist() == eng.ctx_len.cpu().tolist()
+    assert ((n_emit == n_acc + 1) & (n_acc >= 0) & (n_acc <= k_b)).all()
+    for b in range(Bn):
+        assert list(toks[b][:n_acc[b]]) == list(drafts[b][:n_acc[b]])          # accepted prefix is the draft prefix
+    M = int(k_b.sum() + Bn)
+    row0 = np.concatenate([[0], np.cumsum(k_b + 1)])
+    d0 = np.concatenate([[0], np.cumsum(k_b)])
+    got = logits[:M].cpu().numpy()
+    assert np.isfinite(got).all()
+    # ---- Tier A on all sequences
+    ua, us = wl["ua"].cpu().numpy(), wl["us"].cpu().numpy()
+    ql = None if wl["q_logits"] is None else wl["q_logits"].float().cpu().numpy()
+    exact, near, _ = compare_sampler(out, got, drafts, k_b, ua, us, ql)
+    assert near <= max(2, 0.03 * Bn), (exact, near)
+    # ---- Tier B / C on sampled sequences
+    od = oracle_desc(desc)
+    wn = oracle_weights_f64(wl["w"])
+    last = wl["last"].cpu().numpy()
+    picks = sample_sequences(ctx, k_b, k_max)
+    worst, oracle_res = 0.0, []
+    for b in picks:
+        ks, vs = [], []
+        for l in range(desc["n_layers"]):
+            kk, vv = eng.kv_read(l, b, 0, int(ctx[b]))
+            ks.append(kk.float().cpu().numpy())
+            vs.append(vv.float().cpu().numpy())
+        c = OD.SeqCache(od)
+        c.fill(ks, vs)
+        k = int(k_b[b])
+        ref = OD.verify_block(od, wn, c, np.concatenate([[last[b]], drafts[b][:k]]))
+        worst = max(worst, float(np.abs(got[row0[b]:row0[b] + k + 1] - ref).max()))
+        oracle_res.append(OA.verify_sequence(ref, drafts[b][:k], ua[b], us[b], None if ql is None else ql[d0[b]:d0[b] + k]))
+        # the rows appended by the step (positions c .. c + k), as read back from the pages
+        for l in range(desc["n_layers"]):
+            kk, vv = eng.kv_read(l, b, int(ctx[b]), k + 1)
+            for dev_rows, ref_rows in ((kk, c.k[l][ctx[b]:]), (vv, c.v[l][ctx[b]:])):
+                # both sides round to bf16 at rest: values that agree before rounding may land one bf16 step (2^-7
+                # relative) apart
+                assert (np.abs(dev_rows.float().cpu().numpy() - ref_rows) <= 2e-2 + 2.0 ** -7 * np.abs(ref_rows)).all()
+    same, diff = tier_c(out, oracle_res, picks)
+    stats = dict(workload=name, rows=M, row_limit=Bn * (k_max + 1), sequences=Bn, sampled=picks,
+                 contexts=[int(ctx[b]) for b in picks], k_b=[int(k_b[b]) for b in picks], logits_max_abs=worst,
+                 tier_a_exact=exact, tier_a_near_tie=near, tier_c_same=same, tier_c_different=diff,
+                 emitted_per_seq=float(n_emit.mean()), drafted_per_seq=float(k_b.mean()))
+    print(stats)
+    assert worst <= TOL_LOGITS[W.BS_BF16], worst
+    return wl, stats, (drafts, k_b)

@@ -60,3 +60,17 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_bench_setup_guard_stops_on_non_finite_logits():
+    """bench.py feeds the library's logits to torch.multinomial during set-up; a non-finite value must end the program
+    on the host (SystemExit naming the step) before it reaches that device-asserting op.  Stub tensors, no GPU."""
+    import torch
+    import bench
+    bench.check_finite(torch.zeros(3, 5), "stub")
+    for bad in (float("inf"), float("-inf"), float("nan")):
+        z = torch.zeros(3, 5)
+        z[1, 2] = bad
+        with pytest.raises(SystemExit) as e:
+            bench.check_finite(z, "set-up decode step 4 of stub")
+        assert "set-up decode step 4" in str(e.value) and e.value.code != 0

@@ -1,62 +1,21 @@
-"""GPU parity at BASELINE's full size, in the launch configuration bench.py times (1.5B shape, 28 layers, batch 64,
+"""GPU parity at full depth in a launch configuration bench.py times (BASELINE configs[1]: 1.5B shape, 28 layers, batch 64,
 context 2048, k = 8, dense bf16 proposal): sampled outputs the oracle can compute one by one.
 
-* logits of two whole sequences (9 rows x 151936 each) against the full-depth fp64 oracle, max-abs <= 2e-2;
+* logits of two whole sequences (9 rows x 151936 each) against the full-depth fp64 oracle, max-abs <= 2e-2, their
+  appended K/V rows, and the end-to-end ids of those sequences against the oracle on its own logits (counted);
 * the sampler decisions of all 64 sequences against the oracle's rule applied to the device's own logits;
-* properties that hold at any size: row packing, committed lengths, emitted counts."""
-import argparse
-
-import numpy as np
+* properties that hold at any size: row packing, committed lengths, emitted counts.
+(The 7B-shape and pool-stress configurations are covered at their real batch sizes, on two-layer slices, in
+tests/test_gpu_launch_sizes.py.)"""
 import pytest
-import torch
 
-from oracle import decoder as OD
-from paper_2605_08862_amd import workloads as W
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
 
 def test_bench_configuration_sampled_parity():
-    import bench
-    args = argparse.Namespace(batch=64, context=2048, k=8, layers=28)
-    wl = bench.build_workload(args)
-    eng, desc, Bn, k = wl["eng"], wl["desc"], wl["B"], wl["k"]
-    eng.ctx_len.copy_(wl["ctx0"])
-    logits = eng.verify_step(wl["slots"], wl["last"], wl["drafts"], wl["draft_len"], k, want_logits=True)
-    out = eng.accept_resample(wl["drafts"], wl["draft_len"], k, wl["ua"], wl["us"], q_logits=wl["q_logits"])
-    eng.kv_commit(wl["slots"], out["n_accepted"] + 1)
-    assert eng.poll_status() == 0
-    n_acc = out["n_accepted"].cpu().numpy()
-    n_emit = out["n_emitted"].cpu().numpy()
-    assert eng.ctx_len.cpu().tolist() == [2048 + int(n) + 1 for n in n_acc]
-    assert ((n_emit == n_acc + 1) & (n_acc >= 0) & (n_acc <= k)).all()
-    drafts = wl["drafts"].cpu().numpy()
-    toks = out["out_tokens"].cpu().numpy()
-    for b in range(Bn):
-        assert list(toks[b][:n_acc[b]]) == list(drafts[b][:n_acc[b]])      # accepted prefix is the draft prefix
-    # ---- Tier A on all sequences: oracle rule on the device's logits
-    got = logits.cpu().numpy()
-    ua, us = wl["ua"].cpu().numpy(), wl["us"].cpu().numpy()
-    ql = wl["q_logits"].float().cpu().numpy()
-    exact, near, _ = H.compare_sampler(out, got, drafts, np.full(Bn, k), ua, us, ql)
-    assert near <= 3, (exact, near)
-    # ---- Tier B on two sequences at full depth
-    od = H.oracle_desc(desc)
-    wn = W.weights_to_numpy(wl["w"])
-    last = wl["last"].cpu().numpy()
-    worst = 0.0
-    for b in (0, Bn - 1):
-        ks, vs = [], []
-        for l in range(desc["n_layers"]):
-            kk, vv = eng.kv_read(l, b, 0, 2048)
-            ks.append(kk.float().cpu().numpy())
-            vs.append(vv.float().cpu().numpy())
-        c = OD.SeqCache(od)
-        c.fill(ks, vs)
-        ref = OD.verify_block(od, wn, c, np.concatenate([[last[b]], drafts[b]]))
-        worst = max(worst, float(np.abs(got[b * (k + 1):(b + 1) * (k + 1)] - ref).max()))
-    print(dict(logits_max_abs=worst, sampler_exact=exact, sampler_near_tie=near,
-               emitted_per_seq=float(n_emit.mean())))
-    assert worst <= H.TOL_LOGITS[W.BS_BF16], worst
-    eng.close()
+    wl, st, _ = H.run_bench_workload_case("s1p5b_b64_c2048_k8")
+    assert st["rows"] == 576 and st["sampled"] == [0, 63]
+    assert wl["desc"]["n_layers"] == 28
+    wl["eng"].close()
