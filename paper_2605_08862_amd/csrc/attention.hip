@@ -28,6 +28,7 @@
 //     halves, and the probabilities are already laid out as the B operand of O^T = V^T P^T.
 // float32 models use the plain kernel in attn_simple.h.
 #include "attn_simple.h"
+#include "attn_wide.h"
 #include "gemm_mfma.h"
 #include <type_traits>
 
@@ -319,7 +320,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const int32_t* __restric
       const int iq = qr / G, hg = qr % G;
       const float inv = 1.0f / lt;                      // row i always sees at least position c + i: lt > 0
       f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
-      const size_t pr = (size_t)unit * ((size_t)RP * q_blocks) + qr;
+      const size_t pr = ((size_t)(item_start[b] + chunk) * Hkv + h) * ((size_t)RP * q_blocks) + qr;   // slot of (sequence, chunk, head)
 #pragma unroll
       for (int j = 0; j < CH / TPR; ++j) {
         const int ch = sub + j * TPR;
@@ -464,11 +465,9 @@ static void launch_shape(const Shape& s, int B, int k_max, int& q_blocks, int& s
   const int units = B * s.Hkv;
   q_blocks = 1;
   if (tiles == 2 && units < 256) q_blocks = 2;
-  // four tiles: two query blocks of two tiles each.  One workgroup per unit (two wave groups of two tiles) leaves
-  // the second group, half of the CU, idle for every sequence with few draft rows; four blocks of one tile
-  // stream every K/V tile through L2 four times (measured, 7B heads: 4 sequences of 60k tokens 137 us with two
-  // blocks against 196 us with four; ragged batch of 128: 627 us against 729 us).
-  if (tiles == 4) q_blocks = 2;
+  // four tiles: one workgroup of eight waves per unit (attn_wide_kernel), every wave one query tile, K/V shared
+  // through LDS.  (Before: two query blocks of two tiles each, four waves, the second reader served by L2; measured
+  // on the ragged batch of 128 sequences, 7B heads: 620 us per layer, matrix unit busy 10 %, waves waiting 36 %.)
   const int qb_forced = g_force_q_blocks;
   if (qb_forced >= 1 && qb_forced <= tiles && tiles % qb_forced == 0) q_blocks = qb_forced;
   s_min = (256 + s.Hkv * q_blocks - 1) / (s.Hkv * q_blocks);
@@ -522,6 +521,32 @@ static void launch_mfma_attn(const Shape& s, const Plan& p, const KvView& kv, in
   if (prof_token) attention_prof_mark(prof_token, st, false);
 }
 
+template <int D>
+static void launch_wide_attn(const Shape& s, const Plan& p, const KvView& kv, int layer, int B, int B_max, const void* q,
+                             const void* k_pages, const void* v_pages, void* out, void* scratch, int s_min,
+                             void* prof_token, hipStream_t st) {
+  constexpr int NF = D / 16 + 2 * (D / 32);
+  size_t lds = (size_t)8 * 32 * (D + 4) * 4 + 2 * 8 * 32 * 4;          // merge: accumulators of 8 waves + statistics
+  const size_t lds_kv = (size_t)2 * 4 * NF * 1024;                     // two buffers x four phases (two query tiles)
+  if (lds < lds_kv) lds = lds_kv;
+  const int n_units = attn_item_capacity(B, s_min) * s.Hkv;
+  int32_t* counters = (int32_t*)scratch;
+  float* part_ml = (float*)((char*)scratch + counters_bytes(s, B_max));
+  float* part_o = part_ml + (size_t)n_units * 128 * 2;
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  auto kern = attn_wide_kernel<D>;
+  static bool attr_set = false;
+  if (!attr_set) { (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr_set = true; }
+  const int cap_w = (n_units + 7) / 8 * 8;
+  const int grid = cap_w < 256 ? cap_w : 256;                          // one workgroup of eight waves per CU
+  if (prof_token) attention_prof_mark(prof_token, st, true);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, p.seq_k, p.seq_c, p.row_start, p.seq_slot, p.attn_meta,
+                     p.item_start, p.item_seq, p.item_chunk, kv.block_table, kv.max_pages, kv.n_pages, n_units, s.Hq,
+                     s.Hkv, scale_log2e, (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o,
+                     part_ml, counters, p.attn_queue + 8 * layer, p.status);
+  if (prof_token) attention_prof_mark(prof_token, st, false);
+}
+
 void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int layer, int B, int B_max, int k_max, int M_max,
                       const void* q, const void* k_pages, const void* v_pages, void* out, void* scratch,
                       void* prof_token, hipStream_t st) {
@@ -541,6 +566,7 @@ void launch_attention(const Shape& s, const Plan& p, const KvView& kv, int layer
   } while (0)
   if (tiles_wg == 1) BS_ATTN(1, 1);
   else if (tiles_wg == 2) BS_ATTN(2, 1);
-  else BS_ATTN(2, 2);
+  else if (s.D == 128) launch_wide_attn<128>(s, p, kv, layer, B, B_max, q, k_pages, v_pages, out, scratch, s_min, prof_token, st);
+  else launch_wide_attn<64>(s, p, kv, layer, B, B_max, q, k_pages, v_pages, out, scratch, s_min, prof_token, st);
 #undef BS_ATTN
 }

@@ -107,8 +107,9 @@ struct Plan {
   int32_t* row_tok;     // [M_max] input token of row r
   int32_t* row_target;  // [M_max] draft token judged by row r (-1: none)
   // attention work list (bf16 models): every sequence's token range is cut into chunks of chunk_tiles 32-token
-  // tiles; item i = (sequence item_seq[i], chunk item_chunk[i]); the items of sequence b are
-  // item_start[b] .. item_start[b+1]-1
+  // tiles; the item at list position i is (sequence item_seq[i], chunk item_chunk[i]) and the list is ordered by
+  // decreasing size (full chunks, then the shorter last chunks).  Sequence b has item_start[b+1] - item_start[b]
+  // chunks; its chunk c owns SLOT item_start[b] + c, by which partial results are addressed
   int32_t* attn_meta;   // [2]   chunk_tiles, number of items
   int32_t* item_start;  // [B+1]
   int32_t* item_seq;    // [item capacity]

@@ -128,7 +128,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   // chunk) items.  T = tiles in total, S0 = max(B, s_min) = items that fill the GPU once:
   //   * lengths within 25 % of their mean: chunk = ceil(1.25 T / S0) if S0 = B (one chunk per sequence: no
   //     partial results), ceil(T / S0) if the batch is smaller than s_min (equal chunks, one round);
-  //   * ragged batch: chunk = ceil(T / 4 S0), four items per workgroup lane, so the lanes end together.
+  //   * ragged batch: chunk = ceil(T / 2 S0): two full-size items per lane of the GPU plus the shorter last chunks,
+  //     which the list hands out last (see the ordering below).
   // sum_b chunks(b) <= B + T / chunk <= B + 4 S0 always (the work list's capacity).
   __shared__ int s_red[256];
   __shared__ int s_cht;
@@ -144,7 +145,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
     for (int i = 0; i < 256; ++i) { T += s_pr[i]; mx = max(mx, s_red[i]); s_valid += s_pt[i]; }
     const int S = max(B, attn_s_min), cap = attn_item_capacity(B, attn_s_min);
     long long cht = (S > B) ? (T + S - 1) / S : (5 * T + 4LL * S - 1) / (4LL * S);
-    if (4LL * mx * s_valid > 5 * T) cht = (T + 4LL * S - 1) / (4LL * S);       // ragged: longest > 1.25 x mean
+    if (4LL * mx * s_valid > 5 * T) cht = (T + 2LL * S - 1) / (2LL * S);       // ragged: longest > 1.25 x mean
     if (attn_force_chunks > 0) cht = (mx + attn_force_chunks - 1) / attn_force_chunks;
     const long long floor_cht = (T + (cap - B) - 1) / (cap - B);      // keeps sum_b ceil(n_b / cht) <= cap
     if (cht < floor_cht) cht = floor_cht;
@@ -153,28 +154,52 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan p, KvView kv, int B, int
   }
   __syncthreads();
   const int cht = s_cht;
+  // Order of the list = order in which the persistent workgroups take the items: every chunk of full size first,
+  // then the last (shorter) chunk of every sequence, longest first (64 size classes), so that the work still
+  // handed out when the queues run dry is the smallest there is.  item_start[b] keeps numbering a sequence's
+  // chunks contiguously (slot item_start[b] + chunk): the partial results are addressed by slot, not by position.
+  __shared__ int s_hist[64], s_base[64];
+  auto chunks_of = [&](int b) { return (tiles_of(b) + cht - 1) / cht; };
+  auto size_class = [&](int rem) { return 63 - min(63, (int)(((long long)rem * 64 - 1) / cht)); };   // rem in 1 .. cht
   {
-    int n = 0;
-    for (int b = b_lo; b < b_hi; ++b) n += (tiles_of(b) + cht - 1) / cht;
-    s_pr[tid] = n;
+    int n = 0, nf = 0;
+    for (int b = b_lo; b < b_hi; ++b) { const int nc = chunks_of(b); n += nc; nf += max(nc - 1, 0); }
+    s_pr[tid] = n; s_pt[tid] = nf;
   }
+  if (tid < 64) s_hist[tid] = 0;
   __syncthreads();
   if (tid == 0) {
-    int n = 0;
-    for (int i = 0; i < 256; ++i) { const int a = s_pr[i]; s_pr[i] = n; n += a; }
+    int n = 0, nf = 0;
+    for (int i = 0; i < 256; ++i) { const int a = s_pr[i], f = s_pt[i]; s_pr[i] = n; s_pt[i] = nf; n += a; nf += f; }
     p.item_start[B] = n;
     p.attn_meta[0] = cht;
     p.attn_meta[1] = n;
+    s_red[0] = nf;                                       // full-size chunks that are not the last of their sequence
   }
   __syncthreads();
   {
-    int n = s_pr[tid];
+    int n = s_pr[tid], pf = s_pt[tid];
     for (int b = b_lo; b < b_hi; ++b) {
       p.item_start[b] = n;
-      const int nc = (tiles_of(b) + cht - 1) / cht;
-      for (int c = 0; c < nc; ++c) { p.item_seq[n + c] = b; p.item_chunk[n + c] = c; }
+      const int nc = chunks_of(b);
+      for (int c = 0; c + 1 < nc; ++c, ++pf) { p.item_seq[pf] = b; p.item_chunk[pf] = c; }
+      if (nc > 0) atomicAdd(&s_hist[size_class(tiles_of(b) - (nc - 1) * cht)], 1);
       n += nc;
     }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int at = s_red[0];
+    for (int i = 0; i < 64; ++i) { s_base[i] = at; at += s_hist[i]; s_hist[i] = 0; }
+  }
+  __syncthreads();
+  for (int b = b_lo; b < b_hi; ++b) {
+    const int nc = chunks_of(b);
+    if (nc == 0) continue;
+    const int cl = size_class(tiles_of(b) - (nc - 1) * cht);
+    const int pos = s_base[cl] + atomicAdd(&s_hist[cl], 1);
+    p.item_seq[pos] = b;
+    p.item_chunk[pos] = nc - 1;
   }
 }
 
