@@ -530,7 +530,6 @@ static void launch_wide_attn(const Shape& s, const Plan& p, const KvView& kv, in
   const size_t lds_kv = (size_t)2 * 4 * NF * 1024;                     // two buffers x four phases (two query tiles)
   if (lds < lds_kv) lds = lds_kv;
   const int n_units = attn_item_capacity(B, s_min) * s.Hkv;
-  int32_t* counters = (int32_t*)scratch;
   float* part_ml = (float*)((char*)scratch + counters_bytes(s, B_max));
   float* part_o = part_ml + (size_t)n_units * 128 * 2;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
@@ -543,7 +542,9 @@ static void launch_wide_attn(const Shape& s, const Plan& p, const KvView& kv, in
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, p.seq_k, p.seq_c, p.row_start, p.seq_slot, p.attn_meta,
                      p.item_start, p.item_seq, p.item_chunk, kv.block_table, kv.max_pages, kv.n_pages, n_units, s.Hq,
                      s.Hkv, scale_log2e, (const f16*)q, (const f16*)k_pages, (const f16*)v_pages, (f16*)out, part_o,
-                     part_ml, counters, p.attn_queue + 8 * layer, p.status);
+                     part_ml, p.attn_queue + 8 * layer, p.status);
+  hipLaunchKernelGGL(attn_wide_merge_kernel<D>, dim3(B * s.Hkv), dim3(512), 0, st, p.seq_k, p.row_start, p.item_start, s.Hq,
+                     s.Hkv, part_o, part_ml, (f16*)out, p.status);
   if (prof_token) attention_prof_mark(prof_token, st, false);
 }
 

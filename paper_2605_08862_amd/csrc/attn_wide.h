@@ -34,8 +34,7 @@ __global__ void __launch_bounds__(512) attn_wide_kernel(const int32_t* __restric
                                                         const f16* __restrict__ q, const f16* __restrict__ k_pages,
                                                         const f16* __restrict__ v_pages, f16* __restrict__ out,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
-                                                        int32_t* __restrict__ counters, int32_t* __restrict__ queue,
-                                                        int32_t* __restrict__ status) {
+                                                        int32_t* __restrict__ queue, int32_t* __restrict__ status) {
   constexpr int KS = D / 16;            // MFMA K-steps of the QK^T product = K fragments of a tile
   constexpr int DT = D / 32;            // 32-wide d tiles of the output; V fragments of a tile = 2 DT
   constexpr int NF = KS + 2 * DT;       // 1 KiB fragments of one K/V tile
@@ -43,9 +42,6 @@ __global__ void __launch_bounds__(512) attn_wide_kernel(const int32_t* __restric
   constexpr int LDO = D + 4;            // row stride (floats) of an accumulator in LDS: 4 banks of skew per row
   constexpr int THREADS = 512;
   extern __shared__ __align__(16) char lds_raw[];
-  constexpr int kListMax = 64;          // units with partials waiting for the next flush
-  __shared__ int s_list[kListMax];
-  __shared__ int s_nlist;
   __shared__ int s_w;
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, wgs_per_xcd = gridDim.x >> 3;
@@ -245,8 +241,6 @@ __global__ void __launch_bounds__(512) attn_wide_kernel(const int32_t* __restric
         }
         if (n_ch > 1 && sub == 0) { part_ml[pr * 2] = mt; part_ml[pr * 2 + 1] = lt; }
       }
-      // several chunks: remember the unit; its partial is published and merged in flush() below
-      if (n_ch > 1 && threadIdx.x == 0) { s_list[s_nlist] = unit; s_nlist = s_nlist + 1; }
     }
   };   // run
 
@@ -258,73 +252,9 @@ __global__ void __launch_bounds__(512) attn_wide_kernel(const int32_t* __restric
     else run(std::integral_constant<int, 2>{}, unit);
   };
 
-  // Merge of the units with several chunks: the LAST workgroup of (sequence, KV head) to publish its partial merges
-  // all of them; nobody waits (see attn_mfma_kernel for the protocol).
-  auto merge_unit = [&](const int unit) {
-    const int item = unit / Hkv, h = unit % Hkv;
-    const int b = item_seq[item];
-    const int n_ch = item_start[b + 1] - item_start[b];
-    const int G = Hq / Hkv, R = (seq_k[b] + 1) * G, row0 = row_start[b];
-    constexpr int TPR = THREADS / RPT, CH = D / 4;       // 4 threads per row
-    const int qr = threadIdx.x / TPR, sub = threadIdx.x % TPR;
-    if (qr >= R) return;
-    const size_t u0 = (size_t)item_start[b] * Hkv + h;           // unit of chunk 0; chunk c is Hkv units further
-    float mt = -INFINITY;
-    for (int cc = 0; cc < n_ch; ++cc) mt = fmaxf(mt, part_ml[((u0 + (size_t)cc * Hkv) * RPT + qr) * 2]);
-    float lt = 0.f;
-    f32x4 acc[CH / TPR];
-#pragma unroll
-    for (int j = 0; j < CH / TPR; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int cc = 0; cc < n_ch; ++cc) {
-      const size_t pc = (u0 + (size_t)cc * Hkv) * RPT + qr;
-      const float m = part_ml[pc * 2];
-      if (m == -INFINITY) continue;
-      const float f = __builtin_amdgcn_exp2f(m - mt);
-      lt += part_ml[pc * 2 + 1] * f;
-#pragma unroll
-      for (int j = 0; j < CH / TPR; ++j) {
-        const f32x4 v = *(const f32x4*)(part_o + pc * D + (sub + j * TPR) * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[j][e] += v[e] * f;
-      }
-    }
-    const int iq = qr / G, hg = qr % G;
-    const float inv = 1.0f / lt;
-    f16* dst = out + (size_t)(row0 + iq) * Hq * D + (size_t)(h * G + hg) * D;
-#pragma unroll
-    for (int j = 0; j < CH / TPR; ++j)
-      *(f16x4*)(dst + (sub + j * TPR) * 4) =
-          to_f16x4_guarded(acc[j][0] * inv, acc[j][1] * inv, acc[j][2] * inv, acc[j][3] * inv, status);
-  };
-  auto flush = [&]() {
-    __syncthreads();
-    const int n = s_nlist;
-    if (n == 0) return;                                 // uniform
-    __threadfence();
-    __syncthreads();
-    if ((int)threadIdx.x < n) {
-      const int unit = s_list[threadIdx.x];
-      const int item = unit / Hkv, h = unit % Hkv, b = item_seq[item];
-      const int n_ch = item_start[b + 1] - item_start[b];
-      int32_t* cnt = counters + (size_t)b * Hkv + h;
-      const int old = atomicAdd(cnt, 1);
-      const bool last = old == n_ch - 1;
-      if (last) *cnt = 0;                               // ready for the next launch (stream order)
-      else s_list[threadIdx.x] = -1;
-    }
-    __syncthreads();
-    __threadfence();
-    for (int i = 0; i < n; ++i)
-      if (s_list[i] >= 0) merge_unit(s_list[i]);
-    __syncthreads();
-    if (threadIdx.x == 0) s_nlist = 0;
-  };
-
-  if (threadIdx.x == 0) s_nlist = 0;
   int w = slot;                                         // position in this XCD's queue
   while (w < total_w) {
     __syncthreads();                                    // LDS of the previous unit is no longer read
-    if (s_nlist == kListMax) flush();
     process(xcd + 8 * w);
     if (total_w <= wgs_per_xcd) break;                  // at most one unit per workgroup: nothing to take
     __syncthreads();
@@ -332,5 +262,63 @@ __global__ void __launch_bounds__(512) attn_wide_kernel(const int32_t* __restric
     __syncthreads();
     w = __builtin_amdgcn_readfirstlane(s_w);
   }
-  flush();
+}
+
+// Second, small launch of the wide path: one workgroup per (sequence, KV head) combines the partial results of a
+// sequence that was cut into several chunks (float32 rows + (max, sum) per chunk, slot-addressed) into the final
+// float16 rows; sequences with one chunk were written by attn_wide_kernel itself and their workgroups exit at once.
+// (Merging inside the attention kernel by the last workgroup to arrive, as attn_mfma_kernel does, needs a
+// device-scope fence per publication: once per unit it tripled the kernel's time on the long-tail batch, once per
+// workgroup it left every merge to the end of the kernel, 80 us mean / 118 us worst per workgroup with nothing
+// streaming meanwhile.  The kernel boundary orders the partial results for free.)
+template <int D>
+__global__ void __launch_bounds__(512) attn_wide_merge_kernel(const int32_t* __restrict__ seq_k, const int32_t* __restrict__ row_start,
+                                                              const int32_t* __restrict__ item_start, int Hq, int Hkv,
+                                                              const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                              f16* __restrict__ out, int32_t* __restrict__ status) {
+  constexpr int RPT = 128, TPR = 512 / RPT, CH = D / 4, CPT = CH / TPR;   // 4 threads per row, CPT 16-byte chunks each
+  const int b = blockIdx.x / Hkv, h = blockIdx.x % Hkv;
+  const int n_ch = item_start[b + 1] - item_start[b];
+  const int k = seq_k[b];
+  if (n_ch <= 1 || k < 0) return;
+  const int G = Hq / Hkv, R = (k + 1) * G;
+  const int qr = threadIdx.x / TPR, sub = threadIdx.x % TPR;
+  if (qr >= R) return;
+  const size_t u0 = (size_t)item_start[b] * Hkv + h;             // slot of chunk 0; chunk c is Hkv slots further
+  float mt = -INFINITY;
+  for (int cc = 0; cc < n_ch; ++cc) mt = fmaxf(mt, part_ml[((u0 + (size_t)cc * Hkv) * RPT + qr) * 2]);
+  float lt = 0.f;
+  f32x4 acc[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // two chunks per round: their loads are requested together (chunk order of the sums is kept)
+  for (int c0 = 0; c0 < n_ch; c0 += 2) {
+    float m2[2], l2[2];
+    f32x4 v[2][CPT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const size_t pc = (u0 + (size_t)min(c0 + u, n_ch - 1) * Hkv) * RPT + qr;
+      m2[u] = part_ml[pc * 2];
+      l2[u] = part_ml[pc * 2 + 1];
+#pragma unroll
+      for (int j = 0; j < CPT; ++j) v[u][j] = *(const f32x4*)(part_o + pc * D + (sub + j * TPR) * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (c0 + u >= n_ch || m2[u] == -INFINITY) continue;
+      const float f = __builtin_amdgcn_exp2f(m2[u] - mt);
+      lt += l2[u] * f;
+#pragma unroll
+      for (int j = 0; j < CPT; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] += v[u][j][e] * f;
+    }
+  }
+  const int iq = qr / G, hg = qr % G;
+  const float inv = 1.0f / lt;
+  f16* dst = out + (size_t)(row_start[b] + iq) * Hq * D + (size_t)(h * G + hg) * D;
+#pragma unroll
+  for (int j = 0; j < CPT; ++j)
+    *(f16x4*)(dst + (sub + j * TPR) * 4) =
+        to_f16x4_guarded(acc[j][0] * inv, acc[j][1] * inv, acc[j][2] * inv, acc[j][3] * inv, status);
 }
