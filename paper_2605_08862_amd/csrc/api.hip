@@ -398,7 +398,7 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
   launch_plan(p, c->kv, B, k_max, s.V, seq_slot, last_token, draft_tokens, draft_len, true, attn_s_min, attn_force, s.L, st);
   launch_embed(s, p, M_max, c->embed, c->h, c->inv_freq, c->rope_cos, c->rope_sin, st);
   const bool slab_mode = s.dtype == BS_BF16;   // float32 epilogues go through K-split slabs (see gemm.hip)
-  int pending = 0;                              // slabs of the last residual projection not yet added to h
+  SlabRule pending{0, 0, 0, 0, 0};              // slabs of the last residual projection not yet added to h
   for (int l = 0; l < s.L; ++l) {
     { ProfScope ps(c, BS_PROF_EMPTY, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->attn_norm[l], c->a, st);
@@ -416,14 +416,14 @@ bs_status bs_verify_step(bs_ctx* c, int B, const int32_t* seq_slot, const int32_
     launch_attention(s, p, c->kv, l, B, c->B_max, k_max, M_max, c->q, c->k_pages[l], c->v_pages[l], c->attn_out, c->attn_scratch,
                      c->prof_class == BS_PROF_ATTENTION ? (void*)c : nullptr, st);
     { ProfScope ps(c, BS_PROF_GEMM_O, st);
-      pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, nullptr, c->wo[l],
-                            slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
+      pending = launch_gemm_resid(s.dtype, p.n_rows, M_max, s.d, s.Hq * s.D, c->attn_out, c->wo[l],
+                                  slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
     launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->mlp_norm[l], c->a, st);
     { ProfScope ps(c, BS_PROF_GEMM_GATE_UP, st);
       launch_gemm(s.dtype, EPI_SWIGLU, p.n_rows, M_max, s.F, s.d, c->a, nullptr, c->w_gate_up[l], c->act, p.status, st); }
     { ProfScope ps(c, BS_PROF_GEMM_DOWN, st);
-      pending = launch_gemm(s.dtype, EPI_RESID_ADD, p.n_rows, M_max, s.d, s.F, c->act, nullptr, c->w_down[l],
-                            slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
+      pending = launch_gemm_resid(s.dtype, p.n_rows, M_max, s.d, s.F, c->act, c->w_down[l],
+                                  slab_mode ? (void*)c->slabs : (void*)c->h, p.status, st); }
   }
   launch_rmsnorm(s, p, M_max, c->h, c->slabs, pending, c->final_norm, c->hf, st);
   if (logits_debug && s.dtype == BS_F32)

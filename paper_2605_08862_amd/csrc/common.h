@@ -150,7 +150,8 @@ void launch_kv_lengths(const KvView& kv, int B, const int32_t* seq_slot, int32_t
 void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, float* h, const double* inv_freq,
                   float* cos_t, float* sin_t, hipStream_t st);
 // h[r] += sum of n_slabs slabs [M_max, d] (n_slabs may be 0), then out[r] = RMSNorm(h[r]).
-void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
+struct SlabRule;
+void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, const SlabRule& n_slabs,
                     const float* gain, void* out, hipStream_t st);
 // qkv is the float32 projection, given as n_slabs >= 1 slabs [M_max, Nqkv] that are summed.
 // inv_freq: [D/2] float64 table written by launch_rope_table.
@@ -172,7 +173,26 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2, EPI_STORE_
 // slab buffer [split][M_max][N] and the consumer sums the slabs), or 0 when `out` was updated in place
 // (float32 models).
 constexpr int kMaxGemmSplit = 8;
+// Number of K-split slabs a float32-epilogue GEMM writes: fixed on the host (bm == 0), or decided on the DEVICE from
+// the step's row count M, which only the device knows (draft lengths may come straight from the lookup kernel): the
+// launch is sized for the row limit, the kernel and the consumer of the slabs both evaluate slabs(M).  The rule: as
+// many K splits (at most 4, at least 4 K tiles each) as keep all workgroups of the live row blocks resident at once.
+__host__ __device__ __forceinline__ int gemm_adaptive_split(int tiles, int nk, int cap) {
+  int s = tiles > 0 ? cap / tiles : 1;
+  if (s > 4) s = 4;
+  if (s > nk / 4) s = nk / 4;
+  return s < 1 ? 1 : s;
+}
+struct SlabRule {
+  int fixed;                    // slab count when bm == 0 (0: the output was updated in place)
+  int bm, n_blocks, nk, cap;    // device rule: row tile, column blocks, K tiles, resident workgroups
+  __host__ __device__ int slabs(int M) const {
+    return bm == 0 ? fixed : gemm_adaptive_split(((M + bm - 1) / bm) * n_blocks, nk, cap);
+  }
+};
 // status: the step's device status word (float16-range faults of the float16 epilogues).
+SlabRule launch_gemm_resid(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const void* W,
+                           void* out, int32_t* status, hipStream_t st);
 int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K,
                 const void* A, const int32_t* a_rows /*optional gather*/, const void* W, void* out,
                 int32_t* status, hipStream_t st);

@@ -56,11 +56,12 @@ template <> struct Vec4<f16> { typedef _Float16 type __attribute__((ext_vector_t
 
 template <typename T, int NV>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(Plan p, int d, float eps, float* __restrict__ h,
-                                                      const float* __restrict__ slabs, int n_slabs, size_t slab_stride,
+                                                      const float* __restrict__ slabs, SlabRule rule, size_t slab_stride,
                                                       const float* __restrict__ gain, T* __restrict__ out) {
   __shared__ float red[4];
   const int r = blockIdx.x;
-  const int n_rows = p.n_rows[0];                        // waited for only after the row's loads are in flight
+  const int n_rows = p.n_rows[0];                        // a fixed slab count leaves this wait until the row's loads are in flight
+  const int n_slabs = rule.slabs(n_rows);
   typedef float f4 __attribute__((ext_vector_type(4)));
   float* x = h + (size_t)r * d;
   const float* sl = slabs + (size_t)r * d;
@@ -258,7 +259,7 @@ void launch_embed(const Shape& s, const Plan& p, int M_max, const void* embed, f
   else
     hipLaunchKernelGGL(embed_kernel<bf16>, dim3(M_max), dim3(256), 0, st, p, s.d, (const bf16*)embed, h, s.D, inv_freq, cos_t, sin_t);
 }
-void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, int n_slabs,
+void launch_rmsnorm(const Shape& s, const Plan& p, int M_max, float* h, const float* slabs, const SlabRule& n_slabs,
                     const float* gain, void* out, hipStream_t st) {
   const size_t stride = (size_t)M_max * s.d;
 #define BS_RMS(T_, NV_) hipLaunchKernelGGL((rmsnorm_kernel<T_, NV_>), dim3(M_max), dim3(256), 0, st, p, s.d, s.eps, h, slabs, n_slabs, stride, gain, (T_*)out)

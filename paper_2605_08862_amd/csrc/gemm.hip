@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
                                                         const f16* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                         const f16* __restrict__ Wp, void* __restrict__ out,
                                                         int m_blocks, int n_blocks, int n_split, int defer_rows,
-                                                        int32_t* __restrict__ status) {
+                                                        int32_t* __restrict__ status, int adaptive_cap) {
   // accumulators hold C^T tiles (SWAP): a lane owns one activation row and, per group of four
   // registers, four consecutive output columns, so the epilogue stores 8 or 16 bytes per lane
   using G = MfmaGemm<MT, NT, true>;
@@ -135,6 +135,12 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   // rows of the same buffer, each affecting only its own output row - and applies the count to the stores.  A
   // many-round launch reads it first and skips the row blocks beyond it.
   int M = (!defer_rows && n_rows_dev) ? min(*n_rows_dev, M_max) : M_max;
+  if (adaptive_cap > 0) {
+    // The launch is sized for the row limit; the row blocks that are live and the number of K splits follow from
+    // the step's row count (SlabRule: the consumer of the slabs evaluates the same rule)
+    m_blocks = (M + MfmaGemm<MT, NT, true>::BM - 1) / MfmaGemm<MT, NT, true>::BM;
+    n_split = gemm_adaptive_split(m_blocks * n_blocks, K / kBK, adaptive_cap);
+  }
   // XCD-first decoding: the (split, N block, M block) space, M block fastest, is cut into 8 contiguous ranges,
   // one per XCD (workgroup ids are dealt round-robin to the XCDs)
   const int tiles = m_blocks * n_blocks, total = tiles * n_split;
@@ -229,7 +235,7 @@ static void launch_mfma(const int32_t* n_rows_dev, int M_max, int N, int K, cons
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<MT, NT, EPI>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max,
                      N, K, (const f16*)A, a_rows, (const f16*)W, out, m_blocks, n_blocks, n_split, total <= kOneRound ? 1 : 0,
-                     status);
+                     status, 0);
 }
 
 
@@ -418,6 +424,39 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   switch (mt) { case 1: BS_GEMM(1, 2); break; case 2: BS_GEMM(2, 2); break; case 3: BS_GEMM(3, 2); break; case 4: BS_GEMM(4, 2); break; default: BS_GEMM(6, 2); }
 #undef BS_GEMM
   return n_split;
+}
+
+// Residual projections (O, down): float32 K-split slabs, summed into the residual by the next RMSNorm.
+// Above 64 rows: 96-row tiles, two workgroups per CU, 256 output columns per workgroup when the row limit gives
+// enough of them (else 128), and the number of K splits decided on the device from the step's row count: with the
+// split fixed for the row limit B (k_max + 1), a ragged step (1185 of at most 2176 rows, 7B shape) ran the down
+// projection as 140 live workgroups of 128 x 256 on 256 CUs, 239 us; one resident round of 2 x 182 takes 189 us.
+template <int NT>
+static SlabRule launch_resid_adaptive(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const void* W,
+                                      void* out, int32_t* status, hipStream_t st) {
+  using G = MfmaGemm<3, NT, true>;
+  constexpr int nout = 4 * NT * 32, cap = 512;
+  const int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + nout - 1) / nout, nk = K / kBK;
+  const int tiles_max = m_blocks * n_blocks;
+  const int grid = 8 * (((tiles_max > cap ? tiles_max : cap) + 7) / 8);     // tiles(M) * splits(M) never exceeds this
+  static bool attr_set = false;
+  if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<3, NT, EPI_RESID_ADD>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
+  hipLaunchKernelGGL((gemm_mfma_kernel<3, NT, EPI_RESID_ADD>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
+                     (const f16*)A, nullptr, (const f16*)W, out, m_blocks, n_blocks, 1, 0, status, cap);
+  return SlabRule{0, G::BM, n_blocks, nk, cap};
+}
+
+SlabRule launch_gemm_resid(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const void* W,
+                           void* out, int32_t* status, hipStream_t st) {
+  // (up to 640 rows the fixed launches below are tuned for one resident round and start their loads before the row
+  // count arrives; measured at 576 rows, 1.5B shape, the device-side rule costs the down projection 22 -> 27 us)
+  if (dtype == BS_BF16 && M_max > 640 && n_rows_dev) {
+    const int tiles2 = (M_max + 95) / 96 * ((N + 255) / 256);
+    if (tiles2 >= 128) return launch_resid_adaptive<2>(n_rows_dev, M_max, N, K, A, W, out, status, st);
+    return launch_resid_adaptive<1>(n_rows_dev, M_max, N, K, A, W, out, status, st);
+  }
+  const int n = launch_gemm(dtype, EPI_RESID_ADD, n_rows_dev, M_max, N, K, A, nullptr, W, out, status, st);
+  return SlabRule{n, 0, 0, 0, 0};
 }
 
 int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,
