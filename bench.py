@@ -337,6 +337,11 @@ def run_config(name, args, steps, warmup, with_cpu, n_cpu_seq=2):
     filtered = args.top_k > 0 or args.top_p < 1.0
     if filtered:
         wl["eng"].set_filter(args.top_k, args.top_p)
+    # no device fault during set-up; this poll is also the mark between the set-up steps and the measured phase in a
+    # rocprofv3 trace (the status word is cleared by a kernel of its own: see paper_2605_08862_amd/profile_summary.py)
+    fault0 = wl["eng"].poll_status()
+    if fault0 != 0:
+        sys.exit("bench.py: device fault word %d after the set-up of %s" % (fault0, name))
     m = measure(wl, steps, warmup)
     fault = wl["eng"].poll_status()
     cfg = wl["cfg"]
