@@ -138,7 +138,7 @@ __global__ void __launch_bounds__(256, (MT <= 3 ? 2 : 1)) gemm_mfma_kernel(const
   if (adaptive_cap > 0) {
     // The launch is sized for the row limit; the row blocks that are live and the number of K splits follow from
     // the step's row count (SlabRule: the consumer of the slabs evaluates the same rule)
-    m_blocks = (M + MfmaGemm<MT, NT, true>::BM - 1) / MfmaGemm<MT, NT, true>::BM;
+    m_blocks = (M + G::BM - 1) / G::BM;
     n_split = gemm_adaptive_split(m_blocks * n_blocks, K / kBK, adaptive_cap);
   }
   // XCD-first decoding: the (split, N block, M block) space, M block fastest, is cut into 8 contiguous ranges,
