@@ -102,6 +102,10 @@ def kernel_trace(directory, lines):
     return per_class
 
 
+def counter_names(directory):
+    return [r[0] for r in _db(directory).execute("select distinct counter_name from counters_collection order by counter_name")]
+
+
 def counter_pass(directory, lines, title=None):
     c = _db(directory)
     rows = c.execute("select dispatch_id, kernel_name, counter_name, value from counters_collection order by dispatch_id").fetchall()
@@ -146,10 +150,22 @@ def main():
     ap.add_argument("--write", help="directory of the --pmc WRITE_SIZE run (with --copy-calibration)")
     ap.add_argument("--pmc", action="append", default=[], help="directory of a further counter pass (repeatable)")
     ap.add_argument("--bench-log", help="stdout of the kernel-trace run (its JSON line is quoted)")
+    ap.add_argument("--bench-args", default="", help="further bench.py arguments every pass was run with (e.g. '--layers 2')")
     ap.add_argument("--note", action="append", default=[], help="free text for the header (repeatable)")
     args = ap.parse_args()
-    lines = ["rocprofv3 summary of bench.py --config %s (one MI355X).  Written by paper_2605_08862_amd/profile_summary.py; the" % args.workload,
-             "commands are in that file's header.  Only the main phase of the run is counted (set-up steps are cut off)."]
+    lines = ["rocprofv3 summary of bench.py --config %s (one MI355X), written by paper_2605_08862_amd/profile_summary.py." % args.workload,
+             "Only the main phase of each run is counted (set-up steps are cut off).  Commands, each run from /tmp with",
+             "TMPDIR=/tmp and bench.py given by its path in the checkout:"]
+    b = "python3 bench.py --config %s --no-sub --no-cpu-baseline" % args.workload + (" " + args.bench_args if args.bench_args else "")
+    if args.kt:
+        lines.append("  rocprofv3 --kernel-trace --stats -d OUT/kt -o kt -- %s" % b)
+    if args.fetch:
+        lines.append("  rocprofv3 --pmc FETCH_SIZE -d OUT/fetch -o f -- %s --steps 3 --warmup 1 --copy-calibration" % b)
+    if args.write:
+        lines.append("  rocprofv3 --pmc WRITE_SIZE -d OUT/write -o w -- %s --steps 3 --warmup 1 --copy-calibration" % b)
+    for directory in args.pmc:
+        lines.append("  rocprofv3 --pmc %s -d OUT/pmc -o p -- %s --steps 3 --warmup 1" % (" ".join(counter_names(directory)), b))
+    lines.append("  python3 -m paper_2605_08862_amd.profile_summary --workload %s ... (the directories above) > this file" % args.workload)
     lines += args.note
     bench = None
     if args.bench_log:
