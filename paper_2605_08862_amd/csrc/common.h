@@ -186,8 +186,24 @@ __host__ __device__ __forceinline__ int gemm_adaptive_split(int tiles, int nk, i
 struct SlabRule {
   int fixed;                    // slab count when bm == 0 (0: the output was updated in place)
   int bm, n_blocks, nk, cap;    // device rule: row tile, column blocks, K tiles, resident workgroups
+  int bm_alt;                   // second row tile the producer may choose on the device (0: none)
+  // Row tile of the step: with two candidates, the one whose launch is shorter by this model: all workgroups of a
+  // round run at once, a workgroup's time ~ rows of its tile x K tiles of its split, and the 128-row loop does
+  // about 5 % more work per unit of time.
+  __host__ __device__ int tile_rows(int M) const {
+    if (bm_alt == 0) return bm;
+    long cost[2];
+    for (int i = 0; i < 2; ++i) {
+      const int b = i ? bm_alt : bm, tiles = ((M + b - 1) / b) * n_blocks, s = gemm_adaptive_split(tiles, nk, cap);
+      const int rounds = (tiles * s + cap - 1) / cap;
+      cost[i] = (long)b * ((nk + s - 1) / s) * (rounds > 0 ? rounds : 1) * (b == 128 ? 19 : 20);
+    }
+    return cost[1] < cost[0] ? bm_alt : bm;
+  }
   __host__ __device__ int slabs(int M) const {
-    return bm == 0 ? fixed : gemm_adaptive_split(((M + bm - 1) / bm) * n_blocks, nk, cap);
+    if (bm == 0) return fixed;
+    const int b = tile_rows(M);
+    return gemm_adaptive_split(((M + b - 1) / b) * n_blocks, nk, cap);
   }
 };
 // status: the step's device status word (float16-range faults of the float16 epilogues).

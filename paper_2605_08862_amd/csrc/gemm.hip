@@ -3,6 +3,7 @@
 // bf16 models run on the f16 MFMA main loop of gemm_mfma.h over packed weights; float32 models (the
 // tiny parity configuration, launch-latency bound) run on a plain LDS-tiled FMA kernel.
 #include "gemm_mfma.h"
+#include "gemm_ring2.h"
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 // same function with the hardware reciprocal (1 ulp): used in the MFMA epilogue, where a full-precision
@@ -321,6 +322,154 @@ __global__ void __launch_bounds__(512) gemm8_kernel(const int32_t* __restrict__ 
   }
 }
 
+// Large-batch kernels (row limit above 640) on the MfmaGemmRing2 loop: 128 rows x 8 weight row tiles per workgroup,
+// two workgroups per CU.  The row count is read first (these launches run several rounds of the CUs) and row blocks
+// beyond it exit.
+//
+// SwiGLU: wave w holds the gate tile and the up tile of features 32 w .. 32 w + 31 of the block's 128 features.
+__global__ void __launch_bounds__(256, 2) gemm_ring2_swiglu_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
+                                                                  const f16* __restrict__ A, const f16* __restrict__ Wp,
+                                                                  f16* __restrict__ out, int m_blocks, int n_blocks,
+                                                                  int32_t* __restrict__ status) {
+  using G = MfmaGemmRing2;
+  extern __shared__ __align__(16) char lds[];
+  const int M = min(*n_rows_dev, M_max);
+  const int total = m_blocks * n_blocks, per_xcd = (total + 7) / 8;
+  const int id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;      // XCD-first decoding, M block fastest
+  if ((int)(blockIdx.x / 8) >= per_xcd || id >= total) return;
+  const int mb = id % m_blocks, nb = id / m_blocks;
+  const int m0 = mb * G::BM;
+  if (m0 >= M) return;
+  // the wave index is made scalar so that the weight stream's base address stays on the scalar unit
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int nk = K / kBK;
+  const int n_tiles = (N + 31) / 32;                    // row tiles of each half of the packed gate/up matrix
+  const int n_wave0 = (nb * 4 + wave) * 32;
+  const int gate_tile = min(n_wave0 / 32, n_tiles - 1);
+  G::Operands op;
+  G::make_operands(op, A, K, m0, M, Wp, nk, gate_tile, gate_tile + n_tiles);
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+  G::run(acc, op, 0, nk, lds);
+  const int ln = lane & 31, lg = lane >> 5;
+  if (n_wave0 >= N) return;                             // N is a multiple of 32: whole tiles only
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int m = m0 + mi * 32 + ln;
+    if (m >= M) continue;
+    f16* dst = out + (size_t)m * N + n_wave0 + 4 * lg;
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      float y[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) y[j] = silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j];
+      *(f16x4*)(dst + 8 * i4) = to_f16x4_guarded(y[0], y[1], y[2], y[3], status);
+    }
+  }
+}
+
+// Residual projections above 640 rows, 256 output columns per workgroup, float32 K-split slabs.  The row tile (96
+// rows on the MfmaGemm<3, 2> loop or 128 rows on the MfmaGemmRing2 loop), the live row blocks and the number of K
+// splits all follow from the step's row count (SlabRule: the consumer of the slabs evaluates the same rule): which
+// tile fills the 512 resident workgroup slots better depends on the row count, which only the device knows
+// (measured, down projection: 7B shape at 1185 rows, 96-row tiles 2 x 182 workgroups 194 us, 128-row tiles 3 x 140
+// workgroups 172 us; 1.5B shape at 3952 rows, 96-row tiles 2 x 252 workgroups 108 us, 128-row tiles 2 x 186 120 us).
+__global__ void __launch_bounds__(256, 2) gemm_resid_kernel(const int32_t* __restrict__ n_rows_dev, int M_max, int N, int K,
+                                                           const f16* __restrict__ A, const f16* __restrict__ Wp,
+                                                           float* __restrict__ out, SlabRule rule) {
+  extern __shared__ __align__(16) char lds[];
+  const int M = min(*n_rows_dev, M_max);
+  const int bm = rule.tile_rows(M);
+  const int m_blocks = (M + bm - 1) / bm, tiles = m_blocks * rule.n_blocks;
+  const int nk = rule.nk;
+  const int n_split = gemm_adaptive_split(tiles, nk, rule.cap);
+  // XCD-first decoding: the (split, N block, M block) space, M block fastest, is cut into 8 contiguous ranges
+  const int total = tiles * n_split, per_xcd = (total + 7) / 8;
+  const int flat = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if ((int)(blockIdx.x / 8) >= per_xcd || flat >= total) return;
+  const int split = flat / tiles, id = flat % tiles;
+  const int mb = id % m_blocks, nb = id / m_blocks;
+  const int m0 = mb * bm;
+  // the wave index is made scalar so that the weight stream's base address stays on the scalar unit
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int ln = lane & 31, lg = lane >> 5;
+  const int n_tiles = (N + 31) / 32;
+  const int n_wave0 = (nb * 4 + wave) * 64;
+  const int tile0 = min(n_wave0 / 32, n_tiles - 1), tile1 = min(n_wave0 / 32 + 1, n_tiles - 1);
+  const int kt0 = (int)((long)nk * split / n_split), kt1 = (int)((long)nk * (split + 1) / n_split);
+  float* dst = out + (size_t)split * M_max * N;
+  auto store = [&](auto& acc, auto mt_tag) {
+    constexpr int MT = decltype(mt_tag)::value;
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+      const int m = m0 + mi * 32 + ln;
+      if (m >= M) continue;
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int n0 = n_wave0 + ni * 32;
+        if (n0 >= N) continue;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          *(f32x4*)(dst + (size_t)m * N + n0 + 8 * i4 + 4 * lg) =
+              f32x4{acc[mi][ni][4 * i4], acc[mi][ni][4 * i4 + 1], acc[mi][ni][4 * i4 + 2], acc[mi][ni][4 * i4 + 3]};
+      }
+    }
+  };
+  if (bm == MfmaGemmRing2::BM) {
+    using G = MfmaGemmRing2;
+    G::Operands op;
+    G::make_operands(op, A, K, m0, M, Wp, nk, tile0, tile1);
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    G::run(acc, op, kt0, kt1, lds);
+    store(acc, std::integral_constant<int, 4>{});
+  } else {
+    using G = MfmaGemm<3, 2, true>;
+    typename G::Operands op;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      int row, g, s;
+      G::chunk_of(i, row, g, s);
+      const int r = min(m0 + row, M - 1);
+      op.x_rows[i] = A + (size_t)r * K + g * 32 + s * 8;
+      op.x_lds[i] = G::chunk_lds_offset(row, g, s);
+    }
+    op.w_tiles[0] = Wp + (size_t)tile0 * nk * kWBlock + lane * 8;
+    op.w_tiles[1] = Wp + (size_t)tile1 * nk * kWBlock + lane * 8;
+    f32x16 acc[3][2];
+#pragma unroll
+    for (int mi = 0; mi < 3; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    G::run(acc, op, kt0, kt1, lds);
+    store(acc, std::integral_constant<int, 3>{});
+  }
+}
+
+// The ring2 kernels address the activation matrix with 32-bit byte offsets.
+static bool ring2_applies(int M_max, int K) { return (size_t)M_max * K * 2 < ((size_t)1 << 32); }
+
+static void launch_ring2_swiglu(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const void* W, void* out,
+                                int32_t* status, hipStream_t st) {
+  using G = MfmaGemmRing2;
+  const int m_blocks = (M_max + G::BM - 1) / G::BM, n_blocks = (N + 127) / 128;
+  const int grid = 8 * ((m_blocks * n_blocks + 7) / 8);
+  hipLaunchKernelGGL(gemm_ring2_swiglu_kernel, dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, N, K, (const f16*)A,
+                     (const f16*)W, (f16*)out, m_blocks, n_blocks, status);
+}
+
 template <int EPI>
 static void launch_gemm8(const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const int32_t* a_rows,
                          const void* W, void* out, int32_t* status, hipStream_t st) {
@@ -367,6 +516,12 @@ static int dispatch(int dtype, const int32_t* n_rows_dev, int M_max, int N, int 
   if (dtype == BS_F32) { launch_simple<float, EPI>(n_rows_dev, M_max, N, K, A, a_rows, W, out, st); return 0; }
   bool small_tiles = false;
   if constexpr (EPI == EPI_SWIGLU) {
+    // large batches: 128-row tiles on the in-place two-tile ring (see gemm_ring2.h), two workgroups per CU
+    // (measured against the 96-row tiles below: 7B shape at 1185 rows 316 -> 302 us, 1.5B shape at 3952 rows 220 -> 216)
+    if (M_max > 640 && n_rows_dev && !a_rows && ring2_applies(M_max, K)) {
+      launch_ring2_swiglu(n_rows_dev, M_max, N, K, A, W, out, status, st);
+      return 1;
+    }
     bool want = true;
     if (M_max > 128) {
       // 192-row tiles, one workgroup per CU, against 96-row tiles, two per CU: whichever needs less time by rounds of
@@ -443,7 +598,7 @@ static SlabRule launch_resid_adaptive(const int32_t* n_rows_dev, int M_max, int 
   if (!attr_set) { (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<3, NT, EPI_RESID_ADD>, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES); attr_set = true; }
   hipLaunchKernelGGL((gemm_mfma_kernel<3, NT, EPI_RESID_ADD>), dim3(grid), dim3(256), G::LDS_BYTES, st, n_rows_dev, M_max, N, K,
                      (const f16*)A, nullptr, (const f16*)W, out, m_blocks, n_blocks, 1, 0, status, cap);
-  return SlabRule{0, G::BM, n_blocks, nk, cap};
+  return SlabRule{0, G::BM, n_blocks, nk, cap, 0};
 }
 
 SlabRule launch_gemm_resid(int dtype, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A, const void* W,
@@ -452,11 +607,22 @@ SlabRule launch_gemm_resid(int dtype, const int32_t* n_rows_dev, int M_max, int 
   // count arrives; measured at 576 rows, 1.5B shape, the device-side rule costs the down projection 22 -> 27 us)
   if (dtype == BS_BF16 && M_max > 640 && n_rows_dev) {
     const int tiles2 = (M_max + 95) / 96 * ((N + 255) / 256);
-    if (tiles2 >= 128) return launch_resid_adaptive<2>(n_rows_dev, M_max, N, K, A, W, out, status, st);
+    if (tiles2 >= 128) {
+      constexpr int cap = 512;
+      const bool dual = ring2_applies(M_max, K);
+      const int n_blocks = (N + 255) / 256, nk = K / kBK;
+      const int tiles_max = (M_max + 95) / 96 * n_blocks;                      // the smaller tile gives more of them
+      const int grid = 8 * (((tiles_max > cap ? tiles_max : cap) + 7) / 8);   // tiles(M) * splits(M) never exceeds this
+      const SlabRule rule{0, 96, n_blocks, nk, cap, dual ? MfmaGemmRing2::BM : 0};
+      constexpr int lds = MfmaGemm<3, 2, true>::LDS_BYTES > MfmaGemmRing2::LDS_BYTES ? MfmaGemm<3, 2, true>::LDS_BYTES : MfmaGemmRing2::LDS_BYTES;
+      hipLaunchKernelGGL(gemm_resid_kernel, dim3(grid), dim3(256), lds, st, n_rows_dev, M_max, N, K, (const f16*)A,
+                         (const f16*)W, (float*)out, rule);
+      return rule;
+    }
     return launch_resid_adaptive<1>(n_rows_dev, M_max, N, K, A, W, out, status, st);
   }
   const int n = launch_gemm(dtype, EPI_RESID_ADD, n_rows_dev, M_max, N, K, A, nullptr, W, out, status, st);
-  return SlabRule{n, 0, 0, 0, 0};
+  return SlabRule{n, 0, 0, 0, 0, 0};
 }
 
 int launch_gemm(int dtype, GemmEpilogue epi, const int32_t* n_rows_dev, int M_max, int N, int K, const void* A,

@@ -46,9 +46,9 @@ def classify(names):
             cls, marker = "attention", "attention"
         elif "qkv_rope_kernel" in n:
             cls = "gemm_qkv"
-        elif "gemm8_kernel" in n or re.search(r"gemm_mfma_kernelILi\dELi\dELi2E", n):
+        elif "gemm8_kernel" in n or "gemm_ring2_swiglu_kernel" in n or re.search(r"gemm_mfma_kernelILi\dELi\dELi2E", n):
             cls, marker = "gemm_gate_up", "gate_up"
-        elif re.search(r"gemm_mfma_kernelILi\dELi\dELi1E", n):
+        elif "gemm_resid_kernel" in n or re.search(r"gemm_mfma_kernelILi\dELi\dELi1E", n):
             cls = "gemm_down" if marker == "gate_up" else "gemm_o"
         elif re.search(r"gemm_mfma_kernelILi\dELi\dELi3E", n):
             cls = "gemm_qkv"                                   # unfused QKV projection (head sizes other than 128)
