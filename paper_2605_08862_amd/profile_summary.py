@@ -139,7 +139,41 @@ def counter_pass(directory, lines, title=None):
         if name.startswith("void at::") or "at::native" in name:
             continue
         lines.append("%-100s %-12s %7d " % (short(name), a[2] or "-", a[0]) + " ".join("%18.1f" % (a[1].get(cn, 0.0) / a[0]) for cn in counters))
+    derived_rates(c, ordered, classes, lines)
     return {cls: {cn: v / n for cn, v in vals.items()} for cls, (n, vals) in per_class.items()}, cal
+
+
+N_XCD, N_CU, N_SIMD = 8, 256, 1024
+
+
+def derived_rates(c, ordered, classes, lines):
+    """Rates that follow from a pass which holds GRBM_GUI_ACTIVE (cycles with the GPU busy, summed over the 8 XCDs)
+    next to unit-busy counters: shader clock = GUI_ACTIVE / 8 / dispatch duration, unit busy shares = busy cycles /
+    (units x GUI_ACTIVE / 8)."""
+    if not ordered or "GRBM_GUI_ACTIVE" not in ordered[0][2]:
+        return
+    dur = dict(c.execute("select dispatch_id, end - start from kernels").fetchall())
+    agg = {}
+    for (did, name, vals), cls in zip(ordered, classes):
+        if not cls or did not in dur:
+            continue
+        a = agg.setdefault((name, cls), [cls, 0, 0.0, {}])
+        a[1] += 1
+        a[2] += dur[did]
+        for cn, v in vals.items():
+            a[3][cn] = a[3].get(cn, 0.0) + v
+    lines.append("")
+    lines.append("== derived per kernel (main phase): duration in this pass, shader clock = GRBM_GUI_ACTIVE / 8 / duration, busy shares ==")
+    lines.append("%-60s %-12s %9s %9s %11s %9s %9s %12s" % ("kernel", "class", "avg_us", "clock_GHz", "MFMA_busy_%", "TA_busy_%", "L2_hit_%", "L2->L1_GB"))
+    for (name, _), (cls, n, ns, v) in sorted(agg.items(), key=lambda kv: -kv[1][2]):
+        if ns / n < 20e3:
+            continue                                             # too short for the busy-cycle counter to mean a clock
+        cyc = v["GRBM_GUI_ACTIVE"] / N_XCD
+        f = lambda num, units: ("%.1f" % (100.0 * v[num] / (units * cyc))) if num in v and cyc else "-"
+        hit = ("%.1f" % (100.0 * v["TCC_HIT_sum"] / (v["TCC_HIT_sum"] + v["TCC_MISS_sum"]))) if "TCC_HIT_sum" in v and "TCC_MISS_sum" in v else "-"
+        l2l1 = ("%.3f" % (v["TCP_TCC_READ_REQ_sum"] * 128.0 / n / 1e9)) if "TCP_TCC_READ_REQ_sum" in v else "-"
+        lines.append("%-60s %-12s %9.1f %9.2f %11s %9s %9s %12s" % (short(name, 60), cls, ns / n / 1e3, cyc / ns if ns else 0.0,
+                                                                   f("SQ_VALU_MFMA_BUSY_CYCLES", N_SIMD), f("TA_TA_BUSY_sum", N_CU), hit, l2l1))
 
 
 def main():
