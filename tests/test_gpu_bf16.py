@@ -81,8 +81,10 @@ def _run_case(desc, ctx_lens, k_b, k_max, seed, temperature=1.0, q_mode="dense",
             for l in range(desc["n_layers"]):
                 k, v = eng.kv_read(l, b, int(ctx_lens[b]), int(k_b[b]) + 1)
                 kr, vr = caches[b].k[l][ctx_lens[b]:], caches[b].v[l][ctx_lens[b]:]
-                assert np.abs(k.float().cpu().numpy() - kr).max() <= 2e-2
-                assert np.abs(v.float().cpu().numpy() - vr).max() <= 2e-2
+                # both sides round to bf16 at rest: values that agree before rounding may land one bf16 step (2^-7
+                # relative) apart, which exceeds the absolute bound once |x| > 2.5 (wide models)
+                assert (np.abs(k.float().cpu().numpy() - kr) <= 2e-2 + 2.0 ** -7 * np.abs(kr)).all()
+                assert (np.abs(v.float().cpu().numpy() - vr) <= 2e-2 + 2.0 ** -7 * np.abs(vr)).all()
     n_acc = out["n_accepted"].cpu().numpy()
     eng.kv_commit(slots, H.dev_i32(n_acc + 1))
     assert eng.ctx_len.cpu().tolist() == [int(c + n + 1) for c, n in zip(ctx_lens, n_acc)]
@@ -136,6 +138,21 @@ def test_mini_many_ragged_sequences():
     ctx[3], ctx[17] = 0, 899
     k_b = [int(x) for x in rng.integers(0, 9, 40)]
     _run_case(desc, ctx_lens=ctx, k_b=k_b, k_max=8, seed=35, check_kv=False)
+
+
+@pytest.mark.parametrize("fill", ["full", "mixed", "plain"])
+def test_wide_model_large_row_limit(fill):
+    """Row limit 48 x 17 = 816 > 640 on a one-layer model that is wide enough (d = 3840) for the large-batch launch
+    paths at a size the oracle still finishes in seconds: the 128-row gate/up kernel, and the residual projections
+    whose row tile and K split are decided on the device from the step's row count.  With every draft block full (816
+    rows) the device rule takes 128-row tiles for the O projection (K = 2048), with mixed lengths (about 430 rows)
+    and with plain decodes only (48 rows) 96-row tiles; the down projection (K = 512) runs unsplit."""
+    desc = W.shape("mini_bf16", n_layers=1, d_model=3840, n_q_heads=16, n_kv_heads=4, d_ffn=512, vocab=640)
+    rng = np.random.default_rng(61)
+    Bn, k_max = 48, 16
+    ctx = [int(x) for x in rng.integers(0, 150, Bn)]
+    k_b = {"full": [16] * Bn, "mixed": [int(x) for x in rng.integers(0, 17, Bn)], "plain": [0] * Bn}[fill]
+    _run_case(desc, ctx_lens=ctx, k_b=k_b, k_max=k_max, seed=61, check_kv=(fill == "mixed"))
 
 
 def test_mini_head_dim_64():
