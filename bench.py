@@ -246,6 +246,23 @@ def profile_traffic(name):
     return out or None
 
 
+def profile_clock(name):
+    """Shader clock (GHz) and matrix-unit busy share of each kernel class's main kernel, as the counter pass of the
+    profile step measured them on a two-layer slice: the `derived` lines of profiles/<workload>_l1_path_counters.txt
+    (GRBM_GUI_ACTIVE / 8 / duration, and SQ_VALU_MFMA_BUSY_CYCLES over 1024 SIMDs x cycles).  Context for the
+    fraction of the published peak, which assumes 2.4 GHz.  None when no such profile is there."""
+    path = os.path.join(ROOT, "profiles", name + "_l1_path_counters.txt")
+    out = {}
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "derived":
+                out[f[1]] = {"shader_clock_ghz": float(f[2]), "matrix_unit_busy": float(f[3])}
+    except OSError:
+        return None
+    return out or None
+
+
 def measure(wl, steps, warmup):
     """Times `steps` steps (wall clock around the whole loop, and per step with events on the step's stream)."""
     for _ in range(warmup):
@@ -305,6 +322,7 @@ def measure_roofline(wl, steps, rows_per_step):
         c["us_per_launch"] = max(c["us_per_launch_events"] - overhead_us, 1e-3)
         c["ms_per_step"] = c["us_per_launch"] * c["launches_per_step"] * 1e-3
     traffic = profile_traffic(wl["name"]) or {}
+    clocks = profile_clock(wl["name"]) or {}
     for c, (bnd, u) in algo.items():
         if c not in per_class:
             continue
@@ -322,11 +340,13 @@ def measure_roofline(wl, steps, rows_per_step):
             pc["achieved"], pc["peak"], pc["unit"] = pc["algorithmic_units"] / t / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s"
         pc["frac_of_peak"] = pc["achieved"] / pc["peak"]
         pc["traffic"] = traffic.get(c)
+        if c in clocks:
+            pc["profile"] = clocks[c]
     dom = max((c for c in per_class if c in algo), key=lambda c: per_class[c]["ms_per_step"])
     pc = per_class[dom]
     return {"roofline": {"kernel": dom, "bound": pc["bound"], "achieved": pc["achieved"], "peak": pc["peak"],
                          "unit": pc["unit"], "frac": pc["frac_of_peak"], "traffic": pc["traffic"],
-                         "algorithmic_units_per_launch": pc["algorithmic_units"],
+                         "profile": pc.get("profile"), "algorithmic_units_per_launch": pc["algorithmic_units"],
                          "us_per_launch": pc["us_per_launch"], "event_pair_overhead_us": overhead_us},
             "kernel_classes": per_class}
 

@@ -165,6 +165,7 @@ def derived_rates(c, ordered, classes, lines):
     lines.append("")
     lines.append("== derived per kernel (main phase): duration in this pass, shader clock = GRBM_GUI_ACTIVE / 8 / duration, busy shares ==")
     lines.append("%-60s %-12s %9s %9s %11s %9s %9s %12s" % ("kernel", "class", "avg_us", "clock_GHz", "MFMA_busy_%", "TA_busy_%", "L2_hit_%", "L2->L1_GB"))
+    seen_cls = {}
     for (name, _), (cls, n, ns, v) in sorted(agg.items(), key=lambda kv: -kv[1][2]):
         if ns / n < 20e3:
             continue                                             # too short for the busy-cycle counter to mean a clock
@@ -174,6 +175,12 @@ def derived_rates(c, ordered, classes, lines):
         l2l1 = ("%.3f" % (v["TCP_TCC_READ_REQ_sum"] * 128.0 / n / 1e9)) if "TCP_TCC_READ_REQ_sum" in v else "-"
         lines.append("%-60s %-12s %9.1f %9.2f %11s %9s %9s %12s" % (short(name, 60), cls, ns / n / 1e3, cyc / ns if ns else 0.0,
                                                                    f("SQ_VALU_MFMA_BUSY_CYCLES", N_SIMD), f("TA_TA_BUSY_sum", N_CU), hit, l2l1))
+        if cls not in seen_cls and "SQ_VALU_MFMA_BUSY_CYCLES" in v:      # the longest kernel of the class; read by bench.py
+            seen_cls[cls] = "derived %s %.3f %.4f" % (cls, cyc / ns, v["SQ_VALU_MFMA_BUSY_CYCLES"] / (N_SIMD * cyc))
+    if seen_cls:
+        lines.append("")
+        lines.append("== per kernel class: shader clock (GHz) and matrix-unit busy share of its main kernel; read by bench.py ==")
+        lines.extend(seen_cls[c] for c in CLASS_ORDER if c in seen_cls)
 
 
 def main():
