@@ -155,6 +155,15 @@ def test_wide_model_large_row_limit(fill):
     _run_case(desc, ctx_lens=ctx, k_b=k_b, k_max=k_max, seed=61, check_kv=(fill == "mixed"))
 
 
+def test_mini_single_sequence_edges():
+    """Degenerate batches: one sequence with no draft (a single query row in the whole step), one sequence with an
+    empty cache and one draft, and a batch in which no sequence has a draft (k_max = 1 is the smallest row limit)."""
+    desc = W.shape("mini_bf16")
+    _run_case(desc, ctx_lens=[37], k_b=[0], k_max=1, seed=71)
+    _run_case(desc, ctx_lens=[0], k_b=[1], k_max=1, seed=72)
+    _run_case(desc, ctx_lens=[64, 0, 5], k_b=[0, 0, 0], k_max=1, seed=73, q_mode="onehot")
+
+
 def test_mini_head_dim_64():
     desc = W.shape("mini_bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, vocab=4096)
     _run_case(desc, ctx_lens=[100, 513, 64], k_b=[3, 8, 8], k_max=8, seed=25)
