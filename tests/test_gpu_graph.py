@@ -86,3 +86,56 @@ def test_step_replays_from_a_hip_graph(shape, q_mode):
         torch.cuda.synchronize(); return (time.perf_counter() - t0) / n * 1e3
     print("eager %.3f ms, graph replay %.3f ms per step (%s, B=%d, k=%d)" % (wall(step), wall(graph.replay), shape, Bn, k_max))
     eng.close()
+
+
+def test_replay_with_changing_row_counts_on_the_large_batch_paths():
+    """The captured step has fixed grids; the row count lives on the device.  On a model wide enough for the
+    large-batch launch paths (row limit 48 x 17 = 816 > 640: 128-row gate/up kernel, residual projections whose tile
+    and K split follow the row count, RMSNorm summing that many slabs) the draft lengths are rewritten between
+    replays - every block full (816 rows), mixed (about 430), no drafts at all (48) - and each replay must equal the
+    eager step on the same inputs bit for bit."""
+    desc = W.shape("mini_bf16", n_layers=1, d_model=3840, n_q_heads=16, n_kv_heads=4, d_ffn=512, vocab=640)
+    Bn, k_max, V = 48, 16, desc["vocab"]
+    rng = np.random.default_rng(43)
+    ctx_lens = [int(x) for x in rng.integers(0, 150, Bn)]
+    eng = _setup(desc, Bn, k_max, ctx_lens, seed=43)
+    ctx0 = H.dev_i32(ctx_lens)
+    slots = H.dev_i32(np.arange(Bn))
+    last, drafts = H.dev_i32(rng.integers(0, V, Bn)), H.dev_i32(rng.integers(0, V, (Bn, k_max)))
+    dl = H.dev_i32([16] * Bn)
+    ua, us = (torch.tensor(a).to(DEV) for a in W.uniforms(6, Bn, k_max))
+
+    def step():
+        eng.ctx_len.copy_(ctx0)
+        eng.verify_step(slots, last, drafts, dl, k_max)
+        out = eng.accept_resample(drafts, dl, k_max, ua, us)
+        eng.kv_commit(slots, out["n_accepted"] + 1)
+        return out
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            out_g = step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    lengths = [[16] * Bn, [int(x) for x in rng.integers(0, 17, Bn)], [0] * Bn, [16] * Bn, [int(x) for x in rng.integers(0, 17, Bn)]]
+    for trial, k_b in enumerate(lengths):
+        dl.copy_(H.dev_i32(k_b))
+        drafts.copy_(H.dev_i32(rng.integers(0, V, (Bn, k_max))))
+        ref = {k: v.clone() for k, v in step().items()}
+        ref_ctx = eng.ctx_len.clone()
+        torch.cuda.synchronize()
+        eng.ctx_len.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(out_g[k], ref[k]), (trial, k)
+        assert torch.equal(eng.ctx_len, ref_ctx), trial
+        assert int(out_g["n_emitted"].sum().item()) >= Bn
+    assert eng.poll_status() == 0
+    eng.close()
