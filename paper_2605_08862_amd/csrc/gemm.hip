@@ -346,31 +346,38 @@ __global__ void __launch_bounds__(256, 2) gemm_ring2_swiglu_kernel(const int32_t
   const int n_tiles = (N + 31) / 32;                    // row tiles of each half of the packed gate/up matrix
   const int n_wave0 = (nb * 4 + wave) * 32;
   const int gate_tile = min(n_wave0 / 32, n_tiles - 1);
-  G::Operands op;
-  G::make_operands(op, A, K, m0, M, Wp, nk, gate_tile, gate_tile + n_tiles);
-  f32x16 acc[4][2];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-  G::run(acc, op, 0, nk, lds);
   const int ln = lane & 31, lg = lane >> 5;
-  if (n_wave0 >= N) return;                             // N is a multiple of 32: whole tiles only
+  // the last row block of a step with at most 64 live rows computes two row tiles instead of four
+  auto tile = [&](auto mt_tag) {
+    constexpr int MT = decltype(mt_tag)::value;
+    using GT = MfmaGemmRing2T<MT>;
+    typename GT::Operands op;
+    GT::make_operands(op, A, K, m0, M, Wp, nk, gate_tile, gate_tile + n_tiles);
+    f32x16 acc[MT][2];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
-    const int m = m0 + mi * 32 + ln;
-    if (m >= M) continue;
-    f16* dst = out + (size_t)m * N + n_wave0 + 4 * lg;
+    for (int mi = 0; mi < MT; ++mi)
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      float y[4];
+      for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) y[j] = silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j];
-      *(f16x4*)(dst + 8 * i4) = to_f16x4_guarded(y[0], y[1], y[2], y[3], status);
+        for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    GT::run(acc, op, 0, nk, lds);
+    if (n_wave0 >= N) return;                           // N is a multiple of 32: whole tiles only
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+      const int m = m0 + mi * 32 + ln;
+      if (m >= M) continue;
+      f16* dst = out + (size_t)m * N + n_wave0 + 4 * lg;
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = silu_fast(acc[mi][0][4 * i4 + j]) * acc[mi][1][4 * i4 + j];
+        *(f16x4*)(dst + 8 * i4) = to_f16x4_guarded(y[0], y[1], y[2], y[3], status);
+      }
     }
-  }
+  };
+  if (M - m0 <= 64) tile(std::integral_constant<int, 2>{});
+  else tile(std::integral_constant<int, 4>{});
 }
 
 // Residual projections above 640 rows, 256 output columns per workgroup, float32 K-split slabs.  The row tile (96

@@ -24,8 +24,11 @@
 #pragma once
 #include "gemm_mfma.h"
 
-struct MfmaGemmRing2 {
-  static constexpr int MT = 4, NT = 2, BM = 128, THREADS = 256, NCH = 4;
+// MT_ = 4 is the tile the launchers count with; MT_ = 2 computes only the upper 64 rows of such a tile (the last row
+// block of a step when at most 64 of its rows are live).
+template <int MT_>
+struct MfmaGemmRing2T {
+  static constexpr int MT = MT_, NT = 2, BM = 32 * MT, THREADS = 256, NCH = MT;
   static constexpr int STAGE_BYTES = MT * 4 * 1024;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
   static constexpr int CHUNK_LDS_STEP = 4096;   // chunk i of a thread lies 32 rows (one row tile) further down
@@ -117,7 +120,7 @@ struct MfmaGemmRing2 {
     if (kt < kt1) body<0>(acc, wreg, xreg, xf, op, kt, kt1, lds);
   }
 
-  // Operands of a workgroup tile: rows m0 .. m0 + 127 of A (clamped to the last live row M - 1), weight row tiles
+  // Operands of a workgroup tile: rows m0 .. m0 + BM - 1 of A (clamped to the last live row M - 1), weight row tiles
   // tile0 and tile1 of the packed matrix for this wave.
   __device__ static __forceinline__ void make_operands(Operands& op, const f16* A, int K, int m0, int M, const f16* Wp,
                                                        int nk, int tile0, int tile1) {
@@ -135,3 +138,4 @@ struct MfmaGemmRing2 {
     op.w_lane = (threadIdx.x & 63) * 16;
   }
 };
+using MfmaGemmRing2 = MfmaGemmRing2T<4>;
